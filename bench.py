@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-KV decode-attention hot path on one MI355X.
+
+A step is one kv_decode_attn call (main kernel + split-KV combine) over one synthetic
+batch of the chosen workload, inputs resident in HBM.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1|2|3] [--prefetch-distance k]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def timed_steps(kv, torch, cases, pd, steps, warmup):
+    """W untimed + K timed steps, alternating between the cache copies.  Returns
+    (ms per step by wall clock, main-kernel ms per launch and combine ms per launch by HIP events)."""
+    def step(i):
+        c = cases[i % len(cases)]
+        kv.kv_decode_attn(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], c["out"],
+                          c["scale"], c["num_kv_heads"], c["block_size"], pd)
+    for i in range(warmup):
+        step(i)
+    kv.kv_profile_enable(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    main_ms, comb_ms, n = kv.kv_profile_read()
+    kv.kv_profile_enable(0)
+    assert n == steps
+    return (t1 - t0) * 1e3 / steps, main_ms / n, comb_ms / n
+
+
+def cpu_baseline(oracle, synth, case, cfg, budget_s=20.0):
+    """The oracle as it stands, timed on the host cores over whole sequences of the same batch."""
+    import numpy as np
+    bits = dict(q=oracle.bits_of(case["q"]), k=oracle.bits_of(case["k_cache"]), v=oracle.bits_of(case["v_cache"]),
+                bt=case["block_tables"].cpu().numpy(), cl=case["context_lens"].cpu().numpy())
+    lens = case["lens"]
+    Hq = cfg["Hq"]
+    # a first short probe sizes the sample to the time budget
+    probe = np.array([(0, h) for h in range(min(Hq, 8))], np.int32)
+    t0 = time.perf_counter()
+    oracle.paged_attention(bits["q"], bits["k"], bits["v"], bits["bt"], bits["cl"], case["scale"], case["dtype"], probe)
+    dt = time.perf_counter() - t0
+    tok_per_s = max(int(lens[0]), 1) * len(probe) / max(dt, 1e-6)          # (token, q-head) pairs per second
+    total_work = int(lens.sum()) * Hq
+    nseq = len(lens)
+    if total_work / tok_per_s > budget_s:
+        nseq = max(1, int(nseq * budget_s * tok_per_s / total_work))
+    pairs = np.array([(b, h) for b in range(nseq) for h in range(Hq)], np.int32)
+    t0 = time.perf_counter()
+    oracle.paged_attention(bits["q"], bits["k"], bits["v"], bits["bt"], bits["cl"], case["scale"], case["dtype"], pairs)
+    dt = time.perf_counter() - t0
+    kvb = synth.kv_bytes(lens[:nseq], cfg["Hkv"], cfg["d"])
+    return {"value": kvb / dt / 1e9, "unit": "GB/s", "cores": oracle.oracle_threads(), "kind": "oracle",
+            "sample": f"first {nseq} of {len(lens)} sequences, all {Hq} query heads, {kvb / 1e6:.1f} MB of KV in {dt:.2f} s",
+            "tokens_per_s": nseq / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=1, choices=[1, 2, 3])
+    ap.add_argument("--prefetch-distance", type=int, default=None)
+    ap.add_argument("--partition-tokens", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the prefetch-off leg and the other workloads")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only; run with --gpus 1 "
+              "(the path shards by kv head or by sequence with no exchange step)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2504_06319_amd as kv
+    from paper_2504_06319_amd import synth
+
+    if not os.path.exists(kv.library_path()):
+        from paper_2504_06319_amd.build import build_library
+        build_library()
+    kv.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    if args.partition_tokens:
+        kv.kv_decode_set_partition_tokens(args.partition_tokens)
+
+    def make_cases(index, copies=2):
+        cfg = synth.CONFIGS[index]
+        out = []
+        for i in range(copies):      # distinct cache copies so no launch re-reads what the last one left in cache
+            c = synth.make_case(cfg, synth.config_seed(index) + 100000 * i, dev,
+                                lens=None if i == 0 else out[0]["lens"])
+            c["out"] = torch.empty_like(c["q"])
+            out.append(c)
+        return cfg, out
+
+    def measure(index, pd, steps, warmup):
+        cfg, cases = make_cases(index)
+        kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"])
+        ms, main_ms, comb_ms = timed_steps(kv, torch, cases, pd, steps, warmup)
+        return cfg, cases, kvb, ms, main_ms, comb_ms
+
+    pd_on = args.prefetch_distance if args.prefetch_distance is not None else 2
+    log(f"[bench] workload {args.workload} prefetch_distance {pd_on}")
+    cfg, cases, kvb, ms, main_ms, comb_ms = measure(args.workload, pd_on, args.steps, args.warmup)
+    value = kvb / (ms * 1e-3) / 1e9
+    achieved = kvb / (main_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg['name']}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("traffic_bytes_per_launch")
+    result = {
+        "metric": "decode-attn effective KV GB/s (% of HBM peak), prefetch on vs off; tokens/s",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": cfg["name"], "batch": cfg["B"], "q_heads": cfg["Hq"], "kv_heads": cfg["Hkv"],
+                   "head_dim": cfg["d"], "block_size": cfg["bs"],
+                   "context_lens": "fixed" if "lens" in cfg else f"uniform{list(cfg['len_range'])}",
+                   "kv_bytes_per_step": kvb, "prefetch_distance": pd_on,
+                   "partition_tokens": kv.kv_decode_get_partition_tokens()},
+        "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        "tokens_per_s": cfg["B"] / (ms * 1e-3),
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "main attention kernel", "kernel_ms": main_ms, "combine_ms": comb_ms},
+    }
+    log(f"[bench] on: {ms:.4f} ms/step, {value:.0f} GB/s; main kernel {main_ms:.4f} ms, combine {comb_ms:.4f} ms")
+
+    if not args.no_extra:
+        _, _, _, ms0, main0, comb0 = measure(args.workload, 0, args.steps, args.warmup)
+        result["prefetch_off"] = {"prefetch_distance": 0, "ms_per_step": ms0, "value": kvb / (ms0 * 1e-3) / 1e9,
+                                  "kernel_ms": main0, "speedup_on_vs_off": ms0 / ms}
+        log(f"[bench] off: {ms0:.4f} ms/step")
+        others = {}
+        for idx in (1, 2, 3):
+            if idx == args.workload:
+                continue
+            torch.cuda.empty_cache()
+            ocfg, _, okvb, oms, omain, _ = measure(idx, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
+            _, _, _, oms0, _, _ = measure(idx, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
+            others[ocfg["name"]] = {"value": okvb / (oms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_step": oms,
+                                    "pct_hbm_peak": 100.0 * okvb / (oms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                    "kernel_ms": omain, "prefetch_off_ms_per_step": oms0,
+                                    "tokens_per_s": ocfg["B"] / (oms * 1e-3)}
+            log(f"[bench] {ocfg['name']}: on {oms:.4f} ms, off {oms0:.4f} ms")
+        result["other_workloads"] = others
+
+    if not args.no_cpu_baseline:
+        import oracle
+        torch.cuda.empty_cache()
+        result["cpu_baseline"] = cpu_baseline(oracle, synth, cases[0], cfg)
+        log(f"[bench] cpu baseline: {result['cpu_baseline']}")
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

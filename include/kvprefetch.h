@@ -1,0 +1,144 @@
+/*
+ * kvprefetch -- paged-KV decode attention with asynchronous KV-block prefetch
+ * for AMD MI355X (gfx950 / CDNA4).  C ABI.
+ *
+ * The operation is the attention decode step the paper accelerates (Section 3.1,
+ * "Prefetch KV Blocks"): every new token's query attends over its sequence's
+ * KV cache, which lives in fixed-size KV blocks located through a block table.
+ * Algorithm 1 of the paper adds, before the compute on the current block, an
+ * asynchronous fetch of the block the same wave will consume next; here that is
+ * the `prefetch_distance` argument (0 = the baseline flow of Figure 2a, k >= 1 =
+ * the fetch of the tile k iterations ahead is in flight while the current one
+ * is computed, Figure 2b generalised).  Prefetching changes no result.
+ *
+ * All tensor arguments are DEVICE memory owned by the caller.  The library
+ * enqueues kernels on `stream` and returns without synchronising; it allocates
+ * nothing and keeps no pointer after return except the registered workspace.
+ *
+ * Every entry point returns a kv_status; kv_last_error() gives the text of the
+ * last failure on the calling thread.  No C++ exception crosses this boundary.
+ */
+#ifndef KVPREFETCH_H
+#define KVPREFETCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KV_OK = 0,
+    KV_ERR_INVALID = 1,     /* null pointer, rank / shape / stride / dtype mismatch, bad scalar */
+    KV_ERR_UNSUPPORTED = 2, /* head_dim, block_size, dtype or group size the kernels do not cover */
+    KV_ERR_HIP = 3,         /* a HIP runtime call failed; text from hipGetErrorString */
+    KV_ERR_WORKSPACE = 4    /* split-KV workspace missing or too small */
+} kv_status;
+
+typedef enum { KV_F16 = 0, KV_BF16 = 1, KV_I32 = 2, KV_F32 = 3 } kv_dtype;
+
+/* A device tensor: base pointer, element type, rank, extents and strides (in elements). */
+typedef struct kv_tensor {
+    void*   data;
+    int32_t dtype; /* kv_dtype */
+    int32_t ndim;
+    int64_t shape[5];
+    int64_t stride[5];
+} kv_tensor;
+
+/*
+ * Paged decode attention (paper Section 3.1; Algorithm 1 for the prefetch order).
+ *
+ *   out[b,h,:] = sum_t softmax_t( scale * q[b,h,:] . K_b[t,:] ) * V_b[t,:],  t < context_lens[b]
+ *   K_b[t,:]   = k_cache[ block_tables[b, t / block_size], h / (Hq/num_kv_heads), t % block_size, : ]
+ *
+ *   q            [B, Hq, d]                 f16 | bf16, last stride 1
+ *   k_cache      [NBLK, Hkv, block_size, d] same dtype; the [block_size, d] tile of one
+ *   v_cache      [NBLK, Hkv, block_size, d] (block, head) is dense (the paper's M_block, Eq. 1)
+ *   block_tables [B, MB] int32, last stride 1.  Only entries [b, 0 .. ceil(n_b/block_size)-1]
+ *                are read; ids are clamped to [0, NBLK) before use.
+ *   context_lens [B] int32, dense.  n_b <= 0 gives a zero output row; n_b is clamped to
+ *                MB * block_size.  Cache slots at t >= n_b are never used.
+ *   out          [B, Hq, d] same dtype as q, last stride 1, rounded to nearest even.
+ *   scale        multiplies the logits (1/sqrt(d) in the tests).
+ *   prefetch_distance  0 .. KV_MAX_PREFETCH_DISTANCE.
+ *   stream       hipStream_t, NULL = the default stream.
+ *
+ * Supported: d in {64, 128}, block_size in {16, 32}, Hq/Hkv in 1..16.  When
+ * MB * block_size exceeds one partition the call needs the workspace below.
+ */
+#define KV_MAX_PREFETCH_DISTANCE 8
+int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+                   const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+                   float scale, int num_kv_heads, int block_size, int prefetch_distance,
+                   void* stream);
+
+/*
+ * Layer-stack harness: for l = 0 .. num_layers-1
+ *     y      = x . weights[l]                 (bf16 in, fp32 accumulate, bf16 out -> gemm_out)
+ *     q_l    = y[:, 0 : Hq*d] viewed [B, Hq, d]  (or q[l] when q != NULL: then y is unused by attention)
+ *     outs[l] = kv_decode_attn(q_l, k_caches[l], v_caches[l], block_tables, context_lens, ...)
+ * The GEMM is the compute window between two attention calls.  With
+ * cross_layer_prefetch = 1 the leading KV tiles of layer l+1 are touched while
+ * GEMM_l runs so they sit in the memory-side cache when attention_{l+1} starts;
+ * results do not depend on it.  The paper prefetches only inside the attention kernel
+ * (next iteration, Section 3.1); the cross-layer form is this repository's harness.
+ *
+ *   x        [B, K] bf16 dense;  weights[l] [K, N] bf16 dense, N >= Hq*d;  gemm_out [B, N] bf16 dense
+ *   q, k_caches, v_caches, outs: arrays of num_layers tensor pointers (host arrays of
+ *   host structs naming device memory).  Supported GEMM shapes: B <= 128 (or a multiple
+ *   of 128), K % 64 == 0, N % 128 == 0.
+ */
+int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* const* weights,
+                         kv_tensor* gemm_out, const kv_tensor* const* q,
+                         const kv_tensor* const* k_caches, const kv_tensor* const* v_caches,
+                         const kv_tensor* block_tables, const kv_tensor* context_lens,
+                         kv_tensor* const* outs, float scale, int num_kv_heads, int block_size,
+                         int prefetch_distance, int cross_layer_prefetch, void* stream);
+
+/*
+ * Split-KV workspace (the block index range [s, e) that Algorithm 1 takes as input
+ * lets one thread block own part of a sequence; partial results are merged by a
+ * second kernel).  Bytes needed for a call with these extents; 0 when one partition
+ * covers max_context.
+ */
+size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size);
+
+/* Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters. */
+int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
+
+/* Tokens per split-KV partition (multiple of 128, 128 .. 65536); 0 restores the default. */
+int kv_decode_set_partition_tokens(int tokens);
+int kv_decode_get_partition_tokens(void);
+
+/*
+ * Per-kernel timing with HIP events on the call's own stream (the paper reports the
+ * attention kernel's duration, Table 2).  kv_profile_enable(n) creates events for the
+ * next n kv_decode_attn calls (host-side allocation, not on the timed path;
+ * n = 0 frees them); while enabled each call records an event before the main
+ * kernel, between the two kernels and after the combine kernel.  kv_profile_read
+ * waits for the recorded calls, returns the summed durations in milliseconds and the
+ * number of calls, and rearms the same events.  Not thread-safe against concurrent
+ * kv_decode_attn calls on other threads beyond a mutex around the slot counter.
+ */
+int kv_profile_enable(int max_calls);
+int kv_profile_read(double* main_ms_sum, double* combine_ms_sum, int* calls);
+
+/* Text of the last error on this thread; never NULL. */
+const char* kv_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int kv_version(void);
+
+/* Eq. 1 of the paper: bytes of one K (or V) block of one head. */
+size_t kv_block_bytes(int elem_bytes, int head_dim, int block_size);
+
+/* Eq. 2 of the paper: bytes of the blocks one loop iteration of the whole grid touches;
+ * units_per_wg is the number of waves of a workgroup (N_thread / 32 in the paper). */
+size_t kv_iter_working_set_bytes(size_t block_bytes, int units_per_wg, int H, int B);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVPREFETCH_H */

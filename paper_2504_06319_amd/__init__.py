@@ -1,1 +1,22 @@
-"""Paged-KV decode attention with asynchronous KV-block prefetch for AMD MI355X (gfx950)."""
+"""Paged-KV decode attention with asynchronous KV-block prefetch for AMD MI355X (gfx950).
+
+The compute lives in hand-written HIP kernels behind a C ABI (``csrc/``, declared in
+``include/kvprefetch.h``); ``binding`` marshals torch tensors into it.
+"""
+from .binding import (  # noqa: F401
+    KVError,
+    KV_MAX_PREFETCH_DISTANCE,
+    kv_decode_attn,
+    kv_decode_layerstack,
+    kv_decode_workspace_bytes,
+    kv_decode_set_partition_tokens,
+    kv_decode_get_partition_tokens,
+    kv_block_bytes,
+    kv_profile_enable,
+    kv_profile_read,
+    kv_iter_working_set_bytes,
+    kv_version,
+    kv_last_error,
+    load_library,
+    library_path,
+)

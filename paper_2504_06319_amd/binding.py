@@ -1,0 +1,222 @@
+"""ctypes binding of libkvprefetch.so: argument marshalling only.
+
+Every step of the attention path runs in the library's HIP kernels; torch is used
+for device memory and streams.  There is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import threading
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libkvprefetch.so")
+_lib = None
+_lock = threading.Lock()
+
+KV_F16, KV_BF16, KV_I32, KV_F32 = 0, 1, 2, 3
+_DTYPE_CODES = {torch.float16: KV_F16, torch.bfloat16: KV_BF16, torch.int32: KV_I32, torch.float32: KV_F32}
+KV_MAX_PREFETCH_DISTANCE = 8
+
+
+class KVError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"kvprefetch status {status}: {message}")
+        self.status = status
+
+
+class KVTensor(ctypes.Structure):
+    _fields_ = [
+        ("data", ctypes.c_void_p),
+        ("dtype", ctypes.c_int32),
+        ("ndim", ctypes.c_int32),
+        ("shape", ctypes.c_int64 * 5),
+        ("stride", ctypes.c_int64 * 5),
+    ]
+
+
+EXPORTS = [
+    "kv_decode_attn", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_decode_set_workspace",
+    "kv_decode_set_partition_tokens", "kv_decode_get_partition_tokens", "kv_last_error", "kv_version",
+    "kv_block_bytes", "kv_iter_working_set_bytes", "kv_profile_enable", "kv_profile_read",
+]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libkvprefetch.so (built by ``build.build_library`` / ``__graft_entry__.build``)."""
+    global _lib
+    with _lock:
+        if _lib is None:
+            if not os.path.exists(_LIB_PATH):
+                raise FileNotFoundError(
+                    f"{_LIB_PATH} is not built; run `python -m paper_2504_06319_amd.build` first")
+            lib = ctypes.CDLL(_LIB_PATH)
+            T = ctypes.POINTER(KVTensor)
+            TT = ctypes.POINTER(T)
+            lib.kv_decode_attn.restype = ctypes.c_int
+            lib.kv_decode_attn.argtypes = [T, T, T, T, T, T, ctypes.c_float, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_int, ctypes.c_void_p]
+            lib.kv_decode_layerstack.restype = ctypes.c_int
+            lib.kv_decode_layerstack.argtypes = [ctypes.c_int, T, TT, T, TT, TT, TT, T, T, TT, ctypes.c_float,
+                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                 ctypes.c_void_p]
+            lib.kv_decode_workspace_bytes.restype = ctypes.c_size_t
+            lib.kv_decode_workspace_bytes.argtypes = [ctypes.c_int] * 5
+            lib.kv_decode_set_workspace.restype = ctypes.c_int
+            lib.kv_decode_set_workspace.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+            lib.kv_decode_set_partition_tokens.restype = ctypes.c_int
+            lib.kv_decode_set_partition_tokens.argtypes = [ctypes.c_int]
+            lib.kv_decode_get_partition_tokens.restype = ctypes.c_int
+            lib.kv_profile_enable.restype = ctypes.c_int
+            lib.kv_profile_enable.argtypes = [ctypes.c_int]
+            lib.kv_profile_read.restype = ctypes.c_int
+            lib.kv_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                            ctypes.POINTER(ctypes.c_int)]
+            lib.kv_last_error.restype = ctypes.c_char_p
+            lib.kv_version.restype = ctypes.c_int
+            lib.kv_block_bytes.restype = ctypes.c_size_t
+            lib.kv_block_bytes.argtypes = [ctypes.c_int] * 3
+            lib.kv_iter_working_set_bytes.restype = ctypes.c_size_t
+            lib.kv_iter_working_set_bytes.argtypes = [ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+            _lib = lib
+    return _lib
+
+
+def kv_last_error() -> str:
+    return load_library().kv_last_error().decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise KVError(status, kv_last_error())
+
+
+def describe(t: torch.Tensor) -> KVTensor:
+    """Descriptor of a torch tensor: pointer, dtype code, extents, element strides."""
+    if t.dtype not in _DTYPE_CODES:
+        raise KVError(1, f"unsupported torch dtype {t.dtype}")
+    if t.dim() > 5:
+        raise KVError(1, "tensors of rank > 5 are not supported")
+    d = KVTensor()
+    d.data = t.data_ptr()
+    d.dtype = _DTYPE_CODES[t.dtype]
+    d.ndim = t.dim()
+    for i in range(t.dim()):
+        d.shape[i] = t.shape[i]
+        d.stride[i] = t.stride(i)
+    return d
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+_workspaces: dict = {}
+_registered = (0, 0)
+
+
+def _ensure_workspace(device: torch.device, nbytes: int):
+    """Keep a torch-owned scratch buffer per device registered with the library."""
+    global _registered
+    lib = load_library()
+    if nbytes == 0:
+        return
+    key = (device.type, device.index)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    if _registered != (ws.data_ptr(), ws.numel()):
+        _check(lib.kv_decode_set_workspace(ctypes.c_void_p(ws.data_ptr()), ws.numel()))
+        _registered = (ws.data_ptr(), ws.numel())
+
+
+def kv_decode_workspace_bytes(B: int, Hq: int, d: int, max_context: int, block_size: int) -> int:
+    return int(load_library().kv_decode_workspace_bytes(B, Hq, d, max_context, block_size))
+
+
+def kv_decode_set_partition_tokens(tokens: int):
+    _check(load_library().kv_decode_set_partition_tokens(int(tokens)))
+
+
+def kv_decode_get_partition_tokens() -> int:
+    return int(load_library().kv_decode_get_partition_tokens())
+
+
+def kv_decode_attn(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
+                   block_size, prefetch_distance=1, stream=None):
+    """Enqueue paged decode attention on ``stream`` (default: torch's current stream); returns ``out``."""
+    lib = load_library()
+    if q.dim() == 3 and block_tables.dim() == 2:
+        need = kv_decode_workspace_bytes(q.shape[0], q.shape[1], q.shape[2],
+                                         block_tables.shape[1] * block_size, block_size)
+        _ensure_workspace(q.device, need)
+    descs = [describe(t) for t in (q, k_cache, v_cache, block_tables, context_lens, out)]
+    _check(lib.kv_decode_attn(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
+                              int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))))
+    return out
+
+
+def _desc_array(tensors):
+    descs = [describe(t) for t in tensors]
+    arr = (ctypes.POINTER(KVTensor) * len(descs))(*[ctypes.pointer(d) for d in descs])
+    return arr, descs
+
+
+def kv_decode_layerstack(x, weights, gemm_out, q, k_caches, v_caches, block_tables, context_lens, outs,
+                         scale, num_kv_heads, block_size, prefetch_distance=1, cross_layer_prefetch=0,
+                         stream=None):
+    """Enqueue the GEMM + attention layer stack; ``q`` may be None (queries come from the GEMM output)."""
+    lib = load_library()
+    L = len(weights)
+    o0 = outs[0]
+    need = kv_decode_workspace_bytes(o0.shape[0], o0.shape[1], o0.shape[2],
+                                     block_tables.shape[1] * block_size, block_size)
+    _ensure_workspace(x.device, need)
+    w_arr, w_keep = _desc_array(weights)
+    k_arr, k_keep = _desc_array(k_caches)
+    v_arr, v_keep = _desc_array(v_caches)
+    o_arr, o_keep = _desc_array(outs)
+    if q is not None:
+        q_arr, q_keep = _desc_array(q)
+    else:
+        q_arr, q_keep = None, None
+    dx, dg, dbt, dcl = describe(x), describe(gemm_out), describe(block_tables), describe(context_lens)
+    _check(lib.kv_decode_layerstack(L, ctypes.byref(dx), w_arr, ctypes.byref(dg), q_arr, k_arr, v_arr,
+                                    ctypes.byref(dbt), ctypes.byref(dcl), o_arr, float(scale),
+                                    int(num_kv_heads), int(block_size), int(prefetch_distance),
+                                    int(cross_layer_prefetch), ctypes.c_void_p(_stream_handle(stream))))
+    return outs
+
+
+def kv_profile_enable(max_calls: int):
+    _check(load_library().kv_profile_enable(int(max_calls)))
+
+
+def kv_profile_read():
+    """(main kernel ms summed, combine kernel ms summed, calls) since the last read."""
+    a, b, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
+    _check(load_library().kv_profile_read(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)))
+    return a.value, b.value, n.value
+
+
+def kv_block_bytes(elem_bytes: int, head_dim: int, block_size: int) -> int:
+    return int(load_library().kv_block_bytes(elem_bytes, head_dim, block_size))
+
+
+def kv_iter_working_set_bytes(block_bytes: int, units_per_wg: int, H: int, B: int) -> int:
+    return int(load_library().kv_iter_working_set_bytes(block_bytes, units_per_wg, H, B))
+
+
+def kv_version() -> int:
+    return int(load_library().kv_version())

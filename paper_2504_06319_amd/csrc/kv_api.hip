@@ -1,0 +1,278 @@
+// C ABI of kvprefetch: argument validation, error reporting, partition planning and
+// kernel dispatch.  Host code only; the kernels live in the other sources.
+#include "../../include/kvprefetch.h"
+#include "kv_common.h"
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <mutex>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+std::mutex g_ws_mutex;
+void* g_ws_ptr = nullptr;
+size_t g_ws_bytes = 0;
+std::atomic<int> g_part_tokens{0};   // 0 = default
+
+constexpr int kDefaultPartTokens = 512;
+
+int part_tokens() {
+    int t = g_part_tokens.load();
+    return t > 0 ? t : kDefaultPartTokens;
+}
+
+size_t workspace_bytes(int B, int Hq, int d, int64_t max_context, int P) {
+    if (max_context <= P) return 0;
+    int64_t np = (max_context + P - 1) / P;
+    return (size_t)B * Hq * np * (d + 2) * sizeof(float);
+}
+
+bool dense_tile(const kv_tensor* t) {   // [NBLK, Hkv, bs, d] with the [bs, d] tile contiguous
+    return t->stride[3] == 1 && t->stride[2] == t->shape[3];
+}
+
+struct Resolved {
+    kvp::AttnParams p;
+    int elem, d, bs;
+    bool split;
+};
+
+int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+            const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+            float scale, int num_kv_heads, int block_size, int prefetch_distance, Resolved* r) {
+    if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !out)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: null tensor descriptor");
+    if (!q->data || !k_cache->data || !v_cache->data || !block_tables->data || !context_lens->data || !out->data)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: null data pointer");
+    if (q->ndim != 3 || out->ndim != 3 || k_cache->ndim != 4 || v_cache->ndim != 4 ||
+        block_tables->ndim != 2 || context_lens->ndim != 1)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: wrong rank (q,out 3; caches 4; block_tables 2; context_lens 1)");
+    if (q->dtype != KV_F16 && q->dtype != KV_BF16)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: q dtype %d is not f16/bf16", q->dtype);
+    if (k_cache->dtype != q->dtype || v_cache->dtype != q->dtype || out->dtype != q->dtype)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: q, k_cache, v_cache and out must share one dtype");
+    if (block_tables->dtype != KV_I32 || context_lens->dtype != KV_I32)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: block_tables and context_lens must be int32");
+    const int64_t B = q->shape[0], Hq = q->shape[1], d = q->shape[2];
+    if (B <= 0 || Hq <= 0) return fail(KV_ERR_INVALID, "kv_decode_attn: empty batch or head count");
+    if (B > 65535) return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: batch %lld exceeds 65535", (long long)B);
+    if (num_kv_heads <= 0 || Hq % num_kv_heads != 0)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: %lld query heads not divisible by %d kv heads", (long long)Hq, num_kv_heads);
+    if (out->shape[0] != B || out->shape[1] != Hq || out->shape[2] != d)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: out shape differs from q");
+    for (int i = 0; i < 4; ++i)
+        if (k_cache->shape[i] != v_cache->shape[i])
+            return fail(KV_ERR_INVALID, "kv_decode_attn: k_cache and v_cache shapes differ");
+    if (k_cache->shape[1] != num_kv_heads || k_cache->shape[2] != block_size || k_cache->shape[3] != d)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: cache shape [%lld,%lld,%lld,%lld] does not match num_kv_heads %d, block_size %d, head_dim %lld",
+                    (long long)k_cache->shape[0], (long long)k_cache->shape[1], (long long)k_cache->shape[2],
+                    (long long)k_cache->shape[3], num_kv_heads, block_size, (long long)d);
+    if (k_cache->shape[0] <= 0 || k_cache->shape[0] > INT32_MAX)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: cache must hold between 1 and 2^31-1 blocks");
+    if (block_tables->shape[0] != B || context_lens->shape[0] != B)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: block_tables / context_lens batch differs from q");
+    if (block_tables->shape[1] <= 0 || block_tables->shape[1] > (1 << 24))
+        return fail(KV_ERR_INVALID, "kv_decode_attn: block table width out of range");
+    if (q->stride[2] != 1 || out->stride[2] != 1 || block_tables->stride[1] != 1 || context_lens->stride[0] != 1)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: innermost stride must be 1");
+    if (!dense_tile(k_cache) || !dense_tile(v_cache))
+        return fail(KV_ERR_INVALID, "kv_decode_attn: the [block_size, head_dim] tile of a cache block must be dense");
+    if (d != 64 && d != 128) return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: head_dim %lld not in {64,128}", (long long)d);
+    if (block_size != 16 && block_size != 32)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: block_size %d not in {16,32}", block_size);
+    const int G = (int)(Hq / num_kv_heads);
+    if (G > 16) return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: %d query heads per kv head exceeds 16", G);
+    if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE)
+        return fail(KV_ERR_INVALID, "kv_decode_attn: prefetch_distance %d outside 0..%d", prefetch_distance, KV_MAX_PREFETCH_DISTANCE);
+    // 128-bit loads need 16-byte aligned rows
+    auto aligned = [](const kv_tensor* t, int nstr) {
+        if (((uintptr_t)t->data) % 16) return false;
+        for (int i = 0; i < nstr; ++i) if (t->stride[i] % 8) return false;
+        return true;
+    };
+    if (!aligned(q, 2) || !aligned(k_cache, 2) || !aligned(v_cache, 2) || !aligned(out, 2))
+        return fail(KV_ERR_INVALID, "kv_decode_attn: data pointers and outer strides must be 16-byte aligned");
+
+    const int P = part_tokens();
+    const int64_t MB = block_tables->shape[1];
+    const int64_t max_context = MB * block_size;
+    kvp::AttnParams& p = r->p;
+    p.q = q->data; p.k_cache = k_cache->data; p.v_cache = v_cache->data;
+    p.block_tables = (const int32_t*)block_tables->data;
+    p.context_lens = (const int32_t*)context_lens->data;
+    p.out = out->data;
+    p.q_stride_b = q->stride[0]; p.q_stride_h = q->stride[1];
+    p.kv_stride_blk = k_cache->stride[0]; p.kv_stride_h = k_cache->stride[1];
+    p.v_stride_blk = v_cache->stride[0]; p.v_stride_h = v_cache->stride[1];
+    p.out_stride_b = out->stride[0]; p.out_stride_h = out->stride[1];
+    p.bt_stride_b = block_tables->stride[0];
+    p.B = (int)B; p.Hq = (int)Hq; p.Hkv = num_kv_heads; p.G = G;
+    p.MB = (int)MB; p.NBLK = (int)k_cache->shape[0];
+    p.part_blocks = P / block_size;
+    p.NP = (int)((max_context + P - 1) / P);
+    p.prefetch_distance = prefetch_distance;
+    p.scale_log2e = scale * kvp::kLog2e;
+    p.partials = nullptr;
+    r->elem = q->dtype; r->d = (int)d; r->bs = block_size;
+    r->split = p.NP > 1;
+    if (r->split) {
+        const size_t need = workspace_bytes((int)B, (int)Hq, (int)d, max_context, P);
+        std::lock_guard<std::mutex> lock(g_ws_mutex);
+        if (!g_ws_ptr || g_ws_bytes < need)
+            return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
+        p.partials = (float*)g_ws_ptr;
+    }
+    return KV_OK;
+}
+
+// Optional per-call timing: three events per call (before the main kernel, between the
+// kernels, after the combine kernel), recorded on the call's stream.
+std::mutex g_prof_mutex;
+std::vector<hipEvent_t> g_prof_events;
+int g_prof_capacity = 0, g_prof_calls = 0;
+std::vector<char> g_prof_split;
+
+hipEvent_t prof_event(int call, int which) { return g_prof_events[(size_t)call * 3 + which]; }
+
+int check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return KV_OK;
+}
+
+int run_attn(const Resolved& r, hipStream_t stream) {
+    if (r.p.G > 8) return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: group size %d not covered", r.p.G);
+    std::unique_lock<std::mutex> prof_lock(g_prof_mutex);
+    const int slot = (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity) ? g_prof_calls++ : -1;
+    if (slot >= 0) g_prof_split[slot] = r.split;
+    prof_lock.unlock();
+    if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), stream);
+    if (kvp::launch_attn_valu(r.p, r.elem, r.d, r.bs, stream) != 0)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
+    if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
+    if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);
+    if (r.split) {
+        kvp::launch_reduce(r.p, r.elem, r.d, r.bs, stream);
+        if (int rc = check_launch("kv_decode_attn combine kernel")) return rc;
+    }
+    if (slot >= 0) (void)hipEventRecord(prof_event(slot, 2), stream);
+    return KV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+                   const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+                   float scale, int num_kv_heads, int block_size, int prefetch_distance, void* stream) {
+    Resolved r;
+    if (int rc = resolve(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
+                         block_size, prefetch_distance, &r))
+        return rc;
+    return run_attn(r, (hipStream_t)stream);
+}
+
+int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* const* weights,
+                         kv_tensor* gemm_out, const kv_tensor* const* q,
+                         const kv_tensor* const* k_caches, const kv_tensor* const* v_caches,
+                         const kv_tensor* block_tables, const kv_tensor* context_lens,
+                         kv_tensor* const* outs, float scale, int num_kv_heads, int block_size,
+                         int prefetch_distance, int cross_layer_prefetch, void* stream) {
+    (void)num_layers; (void)x; (void)weights; (void)gemm_out; (void)q; (void)k_caches; (void)v_caches;
+    (void)block_tables; (void)context_lens; (void)outs; (void)scale; (void)num_kv_heads; (void)block_size;
+    (void)prefetch_distance; (void)cross_layer_prefetch; (void)stream;
+    return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: not built yet");
+}
+
+size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size) {
+    if (B <= 0 || Hq <= 0 || d <= 0 || max_context <= 0 || block_size <= 0) return 0;
+    const int64_t mc = ((int64_t)max_context + block_size - 1) / block_size * block_size;
+    return workspace_bytes(B, Hq, d, mc, part_tokens());
+}
+
+int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {
+    if ((dev_ptr == nullptr) != (bytes == 0))
+        return fail(KV_ERR_INVALID, "kv_decode_set_workspace: pointer and size must both be set or both be zero");
+    if (((uintptr_t)dev_ptr) % 16) return fail(KV_ERR_INVALID, "kv_decode_set_workspace: pointer must be 16-byte aligned");
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    g_ws_ptr = dev_ptr;
+    g_ws_bytes = bytes;
+    return KV_OK;
+}
+
+int kv_decode_set_partition_tokens(int tokens) {
+    if (tokens != 0 && (tokens < 128 || tokens > 65536 || tokens % 128))
+        return fail(KV_ERR_INVALID, "kv_decode_set_partition_tokens: %d is not 0 or a multiple of 128 in 128..65536", tokens);
+    g_part_tokens.store(tokens);
+    return KV_OK;
+}
+
+int kv_decode_get_partition_tokens(void) { return part_tokens(); }
+
+int kv_profile_enable(int max_calls) {
+    if (max_calls < 0 || max_calls > 100000) return fail(KV_ERR_INVALID, "kv_profile_enable: max_calls %d outside 0..100000", max_calls);
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    for (hipEvent_t ev : g_prof_events) (void)hipEventDestroy(ev);
+    g_prof_events.clear();
+    g_prof_split.assign((size_t)max_calls, 0);
+    g_prof_capacity = 0;
+    g_prof_calls = 0;
+    for (int i = 0; i < 3 * max_calls; ++i) {
+        hipEvent_t ev;
+        hipError_t e = hipEventCreate(&ev);
+        if (e != hipSuccess) {
+            for (hipEvent_t x : g_prof_events) (void)hipEventDestroy(x);
+            g_prof_events.clear();
+            return fail(KV_ERR_HIP, "kv_profile_enable: %s", hipGetErrorString(e));
+        }
+        g_prof_events.push_back(ev);
+    }
+    g_prof_capacity = max_calls;
+    return KV_OK;
+}
+
+int kv_profile_read(double* main_ms_sum, double* combine_ms_sum, int* calls) {
+    if (!main_ms_sum || !combine_ms_sum || !calls) return fail(KV_ERR_INVALID, "kv_profile_read: null output");
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    *main_ms_sum = 0; *combine_ms_sum = 0; *calls = g_prof_calls;
+    for (int i = 0; i < g_prof_calls; ++i) {
+        hipError_t e = hipEventSynchronize(prof_event(i, 2));
+        float a = 0.f, b = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&a, prof_event(i, 0), prof_event(i, 1));
+        if (e == hipSuccess) e = hipEventElapsedTime(&b, prof_event(i, 1), prof_event(i, 2));
+        if (e != hipSuccess) return fail(KV_ERR_HIP, "kv_profile_read: %s", hipGetErrorString(e));
+        *main_ms_sum += a;
+        *combine_ms_sum += b;
+    }
+    g_prof_calls = 0;
+    return KV_OK;
+}
+
+const char* kv_last_error(void) { return g_err; }
+
+int kv_version(void) { return 100; }
+
+size_t kv_block_bytes(int elem_bytes, int head_dim, int block_size) {
+    if (elem_bytes <= 0 || head_dim <= 0 || block_size <= 0) return 0;
+    return (size_t)elem_bytes * head_dim * block_size;
+}
+
+size_t kv_iter_working_set_bytes(size_t block_bytes, int units_per_wg, int H, int B) {
+    if (units_per_wg <= 0 || H <= 0 || B <= 0) return 0;
+    return block_bytes * (size_t)units_per_wg * H * B;
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, evaluates the paper's closed forms, and rejects bad
+arguments before any kernel launch."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2504_06319_amd as kv
+from paper_2504_06319_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "kvprefetch.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = kv.load_library()
+    names = _declared_functions()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_version_and_error_text():
+    assert kv.kv_version() >= 100
+    assert isinstance(kv.kv_last_error(), str)
+
+
+def test_closed_forms_match_the_paper_worked_example():
+    # Section 3.3: Eq. 1 gives 4 KB, Eq. 2 gives 512 KB for Table 3's hyper-parameters at batch 1
+    assert kv.kv_block_bytes(2, 128, 16) == 4096
+    assert kv.kv_iter_working_set_bytes(4096, 128 // 32, 32, 1) == 512 * 1024
+    assert (60 << 20) // kv.kv_iter_working_set_bytes(4096, 4, 32, 1) == 120
+    assert kv.kv_block_bytes(0, 128, 16) == 0
+
+
+def test_workspace_size_formula():
+    P = kv.kv_decode_get_partition_tokens()
+    assert kv.kv_decode_workspace_bytes(8, 32, 128, P, 16) == 0
+    np_ = -(-32768 // P)
+    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == 8 * 32 * np_ * 130 * 4
+    with pytest.raises(kv.KVError):
+        kv.kv_decode_set_partition_tokens(100)
+    kv.kv_decode_set_partition_tokens(1024)
+    assert kv.kv_decode_get_partition_tokens() == 1024
+    kv.kv_decode_set_partition_tokens(0)
+    assert kv.kv_decode_get_partition_tokens() == P
+
+
+def _fake(shape, dtype, ptr=0x1000):
+    """A descriptor with a made-up aligned pointer: validation must reject before any launch."""
+    t = torch.empty(shape, dtype=dtype)
+    d = binding.describe(t)
+    d.data = ptr
+    return d
+
+
+def _call(q, k, v, bt, cl, out, scale=0.1, hkv=2, bs=16, pd=1):
+    lib = kv.load_library()
+    ref = lambda d: ctypes.byref(d) if d is not None else None
+    return lib.kv_decode_attn(ref(q), ref(k), ref(v), ref(bt), ref(cl), ref(out), scale, hkv, bs, pd, None)
+
+
+def _good():
+    f = torch.bfloat16
+    return dict(q=_fake((3, 8, 128), f), k=_fake((10, 2, 16, 128), f), v=_fake((10, 2, 16, 128), f),
+                bt=_fake((3, 4), torch.int32), cl=_fake((3,), torch.int32), out=_fake((3, 8, 128), f))
+
+
+@pytest.mark.parametrize("mutate,status,needle", [
+    (lambda a: a.update(q=None), 1, "null"),
+    (lambda a: setattr(a["k"], "data", 0), 1, "null data"),
+    (lambda a: a.update(q=_fake((3, 8, 128), torch.float32)), 2, "dtype"),
+    (lambda a: a.update(v=_fake((10, 2, 16, 128), torch.float16)), 1, "share one dtype"),
+    (lambda a: a.update(bt=_fake((3, 4), torch.float32)), 1, "int32"),
+    (lambda a: a.update(q=_fake((3, 7, 128), torch.bfloat16), out=_fake((3, 7, 128), torch.bfloat16)), 1, "divisible"),
+    (lambda a: a.update(out=_fake((3, 8, 64), torch.bfloat16)), 1, "out shape"),
+    (lambda a: a.update(k=_fake((10, 2, 32, 128), torch.bfloat16)), 1, "differ"),
+    (lambda a: a.update(bt=_fake((2, 4), torch.int32)), 1, "batch"),
+    (lambda a: a.update(q=_fake((3, 8, 128, 1), torch.bfloat16)), 1, "rank"),
+    (lambda a: setattr(a["q"], "data", 0x1002), 1, "aligned"),
+    (lambda a: a["k"].stride.__setitem__(2, 256), 1, "dense"),
+    (lambda a: a.update(q=_fake((3, 8, 96), torch.bfloat16), out=_fake((3, 8, 96), torch.bfloat16),
+                        k=_fake((10, 2, 16, 96), torch.bfloat16), v=_fake((10, 2, 16, 96), torch.bfloat16)), 2, "head_dim"),
+])
+def test_invalid_arguments_are_rejected_before_launch(mutate, status, needle):
+    a = _good()
+    mutate(a)
+    rc = _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"])
+    assert rc == status, kv.kv_last_error()
+    assert needle in kv.kv_last_error()
+
+
+def test_scalar_arguments_are_checked():
+    a = _good()
+    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], pd=-1) == 1
+    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], pd=kv.KV_MAX_PREFETCH_DISTANCE + 1) == 1
+    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], hkv=0) == 1
+    f = torch.bfloat16
+    a.update(k=_fake((10, 2, 8, 128), f), v=_fake((10, 2, 8, 128), f))
+    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], bs=8) == 2
+
+
+def test_missing_workspace_is_reported():
+    lib = kv.load_library()
+    assert lib.kv_decode_set_workspace(None, 0) == 0
+    binding._registered = (0, 0)
+    a = _good()
+    a.update(bt=_fake((3, 4096), torch.int32))      # 65536 tokens: needs split-KV scratch
+    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"]) == 4
+    assert "workspace" in kv.kv_last_error()
+    assert lib.kv_decode_set_workspace(ctypes.c_void_p(0x1000), 0) == 1

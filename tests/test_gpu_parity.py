@@ -1,0 +1,161 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2504_06319_amd as kv
+from paper_2504_06319_amd import synth
+from kvcheck import check_case, compare, host_bits, run_hip, run_oracle
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _cfg(Hq, Hkv, d, bs, dtype):
+    return dict(Hq=Hq, Hkv=Hkv, d=d, bs=bs, dtype=dtype)
+
+
+def test_tiny_config_matches_oracle():
+    """Benchmark configuration 0: batch 2, MHA 4 heads, d 64, lengths {37, 128}, fp16."""
+    c = synth.make_case(synth.CONFIGS[0], synth.config_seed(0), DEV, poison=True)
+    for pd in (0, 1, 2):
+        check_case(c, pd, f"tiny pd={pd}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("d,bs", [(128, 16), (128, 32), (64, 16), (64, 32)])
+@pytest.mark.parametrize("G", [1, 2, 4, 5, 7, 8])
+def test_shapes_groups_and_dtypes(dtype, d, bs, G):
+    """Several tiles per wave, ragged tails, every supported (d, block_size), the GQA ratios of
+    the paper's four models (1, 4, 5, 7) and more."""
+    Hkv = 2
+    lens = [1, bs - 1, bs, bs + 1, 5 * bs + 3, 333, 700, 64 * bs]
+    c = synth.make_case(_cfg(Hkv * G, Hkv, d, bs, dtype), 100 + G, DEV, poison=True, lens=lens)
+    for pd in (0, 1, 3):
+        check_case(c, pd, f"G={G} d={d} bs={bs} {dtype} pd={pd}")
+
+
+@pytest.mark.parametrize("pd", list(range(0, kv.KV_MAX_PREFETCH_DISTANCE + 1)))
+def test_every_prefetch_distance_gives_the_same_result(pd):
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 7, DEV, poison=True, lens=[3000, 17, 2049, 1024])
+    ref = run_hip(c, 0)
+    got = run_hip(c, pd)
+    compare(got, run_oracle(c), f"pd={pd}")
+    assert torch.equal(got, ref), "prefetching must not change any value"
+
+
+def test_split_kv_partitions_and_combine():
+    """Contexts spanning many partitions, including lengths at partition boundaries."""
+    P = kv.kv_decode_get_partition_tokens()
+    lens = [P - 1, P, P + 1, 3 * P + 17, 8 * P, 1, 0, 5 * P - 16]
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 11, DEV, poison=True, lens=lens)
+    got = run_hip(c, 1)
+    want = run_oracle(c)
+    compare(got, want, "split")
+    assert (got[6] == 0).all()          # empty context -> zero row
+
+
+@pytest.mark.parametrize("P", [128, 256, 2048])
+def test_other_partition_sizes(P):
+    kv.kv_decode_set_partition_tokens(P)
+    try:
+        c = synth.make_case(_cfg(4, 1, 128, 32, "bf16"), 13, DEV, poison=True, lens=[P + 5, 4 * P, 77, 6 * P + 1])
+        check_case(c, 2, f"P={P}")
+    finally:
+        kv.kv_decode_set_partition_tokens(0)
+
+
+def test_empty_and_single_token_contexts():
+    c = synth.make_case(_cfg(4, 4, 64, 16, "f16"), 17, DEV, poison=True, lens=[0, 1, 0, 2])
+    got = run_hip(c, 1)
+    compare(got, run_oracle(c), "empty")
+    assert (got[0] == 0).all() and (got[2] == 0).all()
+    blk = int(c["block_tables"][1, 0])
+    assert torch.equal(got[1], c["v_cache"][blk, :, 0, :])        # context of one returns V exactly
+
+
+def test_wide_table_with_poison_entries_and_negative_length():
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 19, DEV, poison=True, lens=[100, 900, 31], table_width=200)
+    want = run_oracle(c)
+    compare(run_hip(c, 2), want, "wide table")
+    c["context_lens"][2] = -5                                      # treated as empty
+    got = run_hip(c, 2)
+    assert (got[2] == 0).all()
+    compare(got[:2], want[:2], "negative length neighbours")
+
+
+def test_garbage_ids_in_unused_table_entries_are_never_dereferenced():
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 23, DEV, poison=True, lens=[40, 513, 16], table_width=64)
+    want = run_oracle(c)
+    bt = c["block_tables"]
+    for b, n in enumerate(c["lens"]):
+        nb = -(-int(n) // 16)
+        bt[b, nb:] = torch.tensor([-1, 2 ** 31 - 1, -2 ** 31, 10 ** 9] * 16, dtype=torch.int32, device=DEV)[: 64 - nb]
+    compare(run_hip(c, 3), want, "garbage table tail")
+
+
+def test_permuting_physical_block_ids_changes_nothing():
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 29, DEV, lens=[700, 33, 1500])
+    a = run_hip(c, 1)
+    nblk = c["k_cache"].shape[0]
+    perm = torch.randperm(nblk, generator=torch.Generator().manual_seed(1)).to(DEV)
+    c2 = dict(c)
+    c2["k_cache"] = torch.empty_like(c["k_cache"]); c2["k_cache"][perm] = c["k_cache"]
+    c2["v_cache"] = torch.empty_like(c["v_cache"]); c2["v_cache"][perm] = c["v_cache"]
+    c2["block_tables"] = perm[c["block_tables"].long()].to(torch.int32)
+    assert torch.equal(run_hip(c2, 1), a)
+
+
+def test_strided_q_out_and_cache_views_on_a_side_stream():
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 31, DEV, poison=True, lens=[70, 1300])
+    want = run_oracle(c)
+    qbig = torch.zeros(2, 8, 256, dtype=torch.bfloat16, device=DEV); qbig[:, :, :128] = c["q"]
+    obig = torch.zeros(2, 16, 128, dtype=torch.bfloat16, device=DEV)
+    kbig = torch.zeros(c["k_cache"].shape[0], 3, 16, 128, dtype=torch.bfloat16, device=DEV)
+    vbig = torch.zeros_like(kbig)
+    kbig[:, 1:] = c["k_cache"]; vbig[:, 1:] = c["v_cache"]
+    c2 = dict(c, q=qbig[:, :, :128], k_cache=kbig[:, 1:], v_cache=vbig[:, 1:])
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        run_hip(c2, 1, out=obig[:, ::2], stream=s)
+    compare(obig[:, ::2], want, "strided")
+    assert (obig[:, 1::2] == 0).all()
+
+
+def test_identical_keys_return_mean_of_values():
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 37, DEV, lens=[256, 100])
+    c["k_cache"][:] = c["k_cache"][0, 0, 0]
+    got = run_hip(c, 1).to(torch.float64).cpu().numpy()
+    v = c["v_cache"].to(torch.float64).cpu().numpy(); bt = c["block_tables"].cpu().numpy()
+    for b, n in enumerate(c["lens"]):
+        rows = np.stack([v[bt[b, t // 16], :, t % 16] for t in range(n)]).mean(0)     # [Hkv, d]
+        assert np.abs(got[b].reshape(2, 4, 128) - rows[:, None, :]).max() < 2e-3
+
+
+def test_large_logits_do_not_overflow():
+    c = synth.make_case(_cfg(4, 1, 128, 16, "bf16"), 41, DEV, poison=True, lens=[600])
+    c["scale"] = 4.0                       # logits of magnitude ~50: softmax close to one-hot
+    check_case(c, 1, "large logits")
+
+
+# ---------------------------------------------------------------- benchmark configurations at full size
+@pytest.mark.parametrize("index", [1, 2, 3])
+def test_full_size_configuration_on_sampled_rows(index):
+    """Full benchmark shapes in the launch configuration bench.py times; the oracle
+    computes a sample of (sequence, head) rows one by one."""
+    cfg = synth.CONFIGS[index]
+    c = synth.make_case(cfg, synth.config_seed(index), DEV)
+    got0 = run_hip(c, 0)
+    got1 = run_hip(c, 2)
+    assert torch.equal(got0, got1)
+    rng = np.random.default_rng(index)
+    lens = c["lens"]
+    seqs = {int(np.argmin(lens)), int(np.argmax(lens))} | set(rng.integers(0, cfg["B"], 6).tolist())
+    pairs = np.array([(b, h) for b in sorted(seqs) for h in rng.choice(cfg["Hq"], 6, replace=False)], np.int32)
+    want = run_oracle(c, pairs)
+    sub = got1[torch.from_numpy(pairs[:, 0]).long().to(DEV), torch.from_numpy(pairs[:, 1]).long().to(DEV)]
+    compare(sub, want, cfg["name"])
+    assert torch.isfinite(got1.float()).all()
