@@ -68,7 +68,7 @@ typedef struct kv_tensor {
  * Supported: d in {64, 128}, block_size in {16, 32}, Hq/Hkv in 1..16.  When
  * MB * block_size exceeds one partition the call needs the workspace below.
  */
-#define KV_MAX_PREFETCH_DISTANCE 8
+#define KV_MAX_PREFETCH_DISTANCE 4
 int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
                    const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
                    float scale, int num_kv_heads, int block_size, int prefetch_distance,

@@ -18,7 +18,7 @@ _lock = threading.Lock()
 
 KV_F16, KV_BF16, KV_I32, KV_F32 = 0, 1, 2, 3
 _DTYPE_CODES = {torch.float16: KV_F16, torch.bfloat16: KV_BF16, torch.int32: KV_I32, torch.float32: KV_F32}
-KV_MAX_PREFETCH_DISTANCE = 8
+KV_MAX_PREFETCH_DISTANCE = 4
 
 
 class KVError(RuntimeError):

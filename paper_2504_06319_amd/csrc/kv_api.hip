@@ -153,13 +153,18 @@ int check_launch(const char* what) {
 }
 
 int run_attn(const Resolved& r, hipStream_t stream) {
-    if (r.p.G > 8) return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: group size %d not covered", r.p.G);
+    if (r.d != 128 && r.p.G > 8)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: group size %d with head_dim %d not covered", r.p.G, r.d);
     std::unique_lock<std::mutex> prof_lock(g_prof_mutex);
     const int slot = (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity) ? g_prof_calls++ : -1;
     if (slot >= 0) g_prof_split[slot] = r.split;
     prof_lock.unlock();
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), stream);
-    if (kvp::launch_attn_valu(r.p, r.elem, r.d, r.bs, stream) != 0)
+    // head_dim 128 runs on the matrix cores with the LDS prefetch ring; head_dim 64 on the vector-ALU kernel
+    const int lrc = r.d == 128 ? kvp::launch_attn_mfma(r.p, r.elem, r.bs, stream)
+                               : kvp::launch_attn_valu(r.p, r.elem, r.d, r.bs, stream);
+    if (lrc == -2) return fail(KV_ERR_HIP, "kv_decode_attn: could not raise the dynamic LDS limit of the kernel");
+    if (lrc != 0)
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);

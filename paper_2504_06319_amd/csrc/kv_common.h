@@ -92,6 +92,7 @@ __device__ __forceinline__ float group_sum(float x) {
 }
 
 int launch_attn_valu(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
+int launch_attn_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream);
 int launch_reduce(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 
 }  // namespace kvp
