@@ -99,18 +99,29 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
 
 /*
  * Split-KV workspace (the block index range [s, e) that Algorithm 1 takes as input
- * lets one thread block own part of a sequence; partial results are merged by a
- * second kernel).  Bytes needed for a call with these extents; 0 when one partition
- * covers max_context.
+ * lets a worker own part of a sequence; partial results are merged by a second
+ * kernel).  Bytes needed for a call with these extents: for head_dim 128 a fixed
+ * bound (two partial pieces per persistent worker), for head_dim 64 one partial per
+ * (sequence, query head, partition), 0 when one partition covers max_context.
  */
 size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size);
 
 /* Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters. */
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
 
-/* Tokens per split-KV partition (multiple of 128, 128 .. 65536); 0 restores the default. */
+/* head_dim 64 path: tokens per split-KV partition (multiple of 128, 128 .. 65536); 0 restores the default. */
 int kv_decode_set_partition_tokens(int tokens);
 int kv_decode_get_partition_tokens(void);
+
+/*
+ * head_dim 128 path: persistent waves (workers) per compute unit, 1 .. 16; 0 restores the
+ * automatic choice.  Each worker holds (prefetch_distance + 1) x 8 KB of LDS, so the
+ * number in effect is capped by the 160 KB of a compute unit (Eq. 2 re-derived for
+ * LDS as the prefetch target: bytes in flight per CU = 8 KB x prefetch_distance x waves);
+ * kv_decode_get_waves_per_cu returns the number a call with that distance would use.
+ */
+int kv_decode_set_waves_per_cu(int waves);
+int kv_decode_get_waves_per_cu(int prefetch_distance);
 
 /*
  * Per-kernel timing with HIP events on the call's own stream (the paper reports the

@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     kv_decode_workspace_bytes,
     kv_decode_set_partition_tokens,
     kv_decode_get_partition_tokens,
+    kv_decode_set_waves_per_cu,
+    kv_decode_get_waves_per_cu,
     kv_block_bytes,
     kv_profile_enable,
     kv_profile_read,

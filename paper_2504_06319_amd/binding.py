@@ -39,7 +39,8 @@ class KVTensor(ctypes.Structure):
 
 EXPORTS = [
     "kv_decode_attn", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_decode_set_workspace",
-    "kv_decode_set_partition_tokens", "kv_decode_get_partition_tokens", "kv_last_error", "kv_version",
+    "kv_decode_set_partition_tokens", "kv_decode_get_partition_tokens", "kv_decode_set_waves_per_cu",
+    "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_profile_enable", "kv_profile_read",
 ]
 
@@ -73,6 +74,10 @@ def load_library():
             lib.kv_decode_set_partition_tokens.restype = ctypes.c_int
             lib.kv_decode_set_partition_tokens.argtypes = [ctypes.c_int]
             lib.kv_decode_get_partition_tokens.restype = ctypes.c_int
+            lib.kv_decode_set_waves_per_cu.restype = ctypes.c_int
+            lib.kv_decode_set_waves_per_cu.argtypes = [ctypes.c_int]
+            lib.kv_decode_get_waves_per_cu.restype = ctypes.c_int
+            lib.kv_decode_get_waves_per_cu.argtypes = [ctypes.c_int]
             lib.kv_profile_enable.restype = ctypes.c_int
             lib.kv_profile_enable.argtypes = [ctypes.c_int]
             lib.kv_profile_read.restype = ctypes.c_int
@@ -151,6 +156,14 @@ def kv_decode_set_partition_tokens(tokens: int):
 
 def kv_decode_get_partition_tokens() -> int:
     return int(load_library().kv_decode_get_partition_tokens())
+
+
+def kv_decode_set_waves_per_cu(waves: int):
+    _check(load_library().kv_decode_set_waves_per_cu(int(waves)))
+
+
+def kv_decode_get_waves_per_cu(prefetch_distance: int) -> int:
+    return int(load_library().kv_decode_get_waves_per_cu(int(prefetch_distance)))
 
 
 def kv_decode_attn(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,

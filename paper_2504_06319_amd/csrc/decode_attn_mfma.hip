@@ -1,10 +1,17 @@
 // Paged decode attention for head_dim 128 on the matrix cores, with an LDS ring that
 // holds the KV tiles a wave will consume next.
 //
-// Work mapping (paper Section 3.1, re-mapped so that a KV byte is fetched once for all
-// grouped query heads): one workgroup per (sequence, kv head, partition [s, e) of the
-// block range); each wave owns one 16-token tile per iteration and walks the range with
-// a stride of the wave count, the walk of Algorithm 1.
+// Work mapping.  The paper's kernel gives a thread block one (query head, sequence) and
+// lets its warps walk a block index range [s, e) (Section 3.1, Algorithm 1).  Here the
+// unit of work is (sequence, kv head): all grouped query heads are served from one fetch
+// of a KV tile.  The 16-token tiles of all units, in (sequence, kv head, tile) order, form
+// one flat index space of T tiles that is cut into equal contiguous ranges, one per wave;
+// a wave is a persistent worker that walks its range [r0, r1) tile by tile (Algorithm 1
+// with one warp per range).  Sequence lengths live on the device, so every wave derives
+// T and its own range from context_lens with a wave-wide scan; nothing returns to the
+// host.  A wave that covers a unit completely writes the output rows itself; a wave whose
+// range cuts a unit writes an unnormalised partial (at most two per wave: the piece at
+// the start and the piece at the end of its range) that the finalize kernel merges.
 //
 // Prefetch (Algorithm 1 generalised to distance PD): a wave owns PD + 1 LDS stages.
 // Per iteration it waits for the current tile, issues the asynchronous global->LDS
@@ -107,34 +114,121 @@ constexpr int kTileTokens = 16;
 constexpr int kRowBytes = 256;                       // 128 x 16-bit
 constexpr int kTileBytes = kTileTokens * kRowBytes;  // 4 KB for K, the same for V
 constexpr int kStageBytes = 2 * kTileBytes;
+constexpr int kD = 128;
+constexpr int kPartialStride = kD + 4;               // floats per partial row: acc[128], max, sum, 2 pad (16-byte rows)
+constexpr int kMaxWorkers = 4096;
 
-template <Elem E, int BS, int PD, int W>
-__global__ __launch_bounds__(W* kWaveSize) void attn_mfma_kernel(AttnParams p) {
-    constexpr int D = 128;
-    constexpr int NS = PD + 1;                  // LDS stages per wave
+// Position of a worker inside the flat tile space; every field is wave-uniform.
+struct Cursor {
+    int b;        // sequence
+    int kvh;      // kv head
+    int j;        // tile index inside the sequence
+    int ntiles;   // tiles of sequence b
+    int n;        // clamped context length of sequence b
+};
+
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;   // uniform loads become scalar loads
+
+__device__ __forceinline__ int clamp_len(int n, int max_len) { return min(max(n, 0), max_len); }
+__device__ __forceinline__ int tiles_of(int n) { return (n + kTileTokens - 1) / kTileTokens; }
+
+__device__ __forceinline__ int wave_sum_i32(int v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// Per-kv-head tile total of the batch, and (optionally) for a flat position `target` the
+// sequence that holds it: the last b whose first flat tile Hkv * cum[b] is <= target.
+struct ScanResult { int total; int b; int cum_b; };
+
+__device__ __forceinline__ int scan_total(const_i32_ptr cl, int B, int max_len, int lane) {
+    int total = 0;
+    for (int base = 0; base < B; base += kWaveSize) {
+        const int idx = base + lane;
+        const int t = idx < B ? tiles_of(clamp_len(cl[idx], max_len)) : 0;
+        total += wave_sum_i32(t);
+    }
+    return total;
+}
+
+__device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len, int lane, int Hkv,
+                                            int64_t target, int& b_out, int& cum_out) {
+    int cum = 0, found_b = 0, found_cum = 0;
+    for (int base = 0; base < B; base += kWaveSize) {
+        const int idx = base + lane;
+        const int t = idx < B ? tiles_of(clamp_len(cl[idx], max_len)) : 0;
+        int incl = t;
+#pragma unroll
+        for (int off = 1; off < kWaveSize; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        const int excl = cum + incl - t;
+        const bool pred = idx < B && (int64_t)Hkv * excl <= target;
+        const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(pred));
+        if (cnt == 0) break;                       // the predicate is monotone: nothing further matches
+        found_b = base + cnt - 1;
+        found_cum = __builtin_amdgcn_readlane(excl, cnt - 1);
+        cum += __builtin_amdgcn_readlane(incl, kWaveSize - 1);
+        if (cnt < kWaveSize) break;
+    }
+    b_out = found_b;
+    cum_out = found_cum;
+}
+
+__device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_workers) {
+    return (int64_t)worker * T / num_workers;
+}
+
+template <Elem E, int BS, int PD>
+__global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
+    constexpr int D = kD;
+    constexpr int NS = PD + 1;                  // LDS stages of the wave
     constexpr int TPB = BS / kTileTokens;       // 16-token tiles per KV block
-    constexpr int LOADS = 8;                    // wave-wide 1 KB loads per tile pair (4 K + 4 V)
+    constexpr int LOADS = 8;                    // wave-wide 1 KB fetches per tile pair (4 K + 4 V)
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-    const int part = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWaveSize);
-    const int lane = tid % kWaveSize;
+    const int worker = blockIdx.x;
+    const int lane = threadIdx.x;
     const int lq = lane / 16, lr = lane % 16;   // lane group (0..3) and index in the group
+    const int G = p.G, Hkv = p.Hkv;
+    const int max_len = p.MB * BS;
+    const_i32_ptr cl = (const_i32_ptr)p.context_lens;
+    const_i32_ptr bt = (const_i32_ptr)p.block_tables;
 
-    int n = p.context_lens[b];
-    n = min(max(n, 0), p.MB * BS);
-    const int ntiles_seq = (n + kTileTokens - 1) / kTileTokens;
-    const int part_tiles = p.part_blocks * TPB;
-    const int s = part * part_tiles;
-    const bool direct = (p.NP == 1);
-    if (s >= ntiles_seq && !(direct && part == 0)) return;
-    const int e = min(ntiles_seq, s + part_tiles);
-    const int G = p.G;
-
-    // ---- Q^T operand: lane (g = lr, lq) holds Q[g][(4j + lq) * 8 .. +8] for j = 0..3, zero rows for g >= G
-    u32x4 qb[4];
+    // ---- this worker's range of the flat tile space
+    const int total = scan_total(cl, p.B, max_len, lane);
+    const int64_t T = (int64_t)total * Hkv;
+    const int64_t r0 = range_start(worker, T, p.num_workers);
+    const int64_t r1 = range_start(worker + 1, T, p.num_workers);
+    if (r0 >= r1) return;
+    Cursor ca;
     {
+        int b0, cum0;
+        scan_locate(cl, p.B, max_len, lane, Hkv, r0, b0, cum0);
+        ca.b = b0;
+        ca.n = clamp_len(cl[b0], max_len);
+        ca.ntiles = tiles_of(ca.n);
+        const int rem = (int)(r0 - (int64_t)Hkv * cum0);
+        ca.kvh = rem / ca.ntiles;
+        ca.j = rem - ca.kvh * ca.ntiles;
+    }
+    auto advance = [&](Cursor& c) {              // step to the next flat tile; the caller knows one exists
+        if (++c.j < c.ntiles) return;
+        c.j = 0;
+        if (++c.kvh < Hkv) return;
+        c.kvh = 0;
+        do {
+            ++c.b;
+            c.n = clamp_len(cl[c.b], max_len);
+            c.ntiles = tiles_of(c.n);
+        } while (c.ntiles == 0 && c.b + 1 < p.B);
+    };
+
+    // ---- Q^T operand of a unit: lane (g = lr, lq) holds Q[g][(4j + lq) * 8 .. +8], zero rows for g >= G
+    u32x4 qb[4];
+    auto load_q = [&](int b, int kvh) {
         const uint16_t* qrow = reinterpret_cast<const uint16_t*>(p.q) + (int64_t)b * p.q_stride_b +
                                (int64_t)(kvh * G + min(lr, G - 1)) * p.q_stride_h;
 #pragma unroll
@@ -142,7 +236,8 @@ __global__ __launch_bounds__(W* kWaveSize) void attn_mfma_kernel(AttnParams p) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(qrow + (4 * j + lq) * 8);
             qb[j] = lr < G ? v : u32x4{0, 0, 0, 0};
         }
-    }
+    };
+    load_q(ca.b, ca.kvh);
 
     // ---- per-lane byte offsets, loop invariant
     // fetch r (0..3) of a tile lands rows 4r..4r+3; this lane lands row t = 4r + lq at LDS slot lr, so it
@@ -164,22 +259,17 @@ __global__ __launch_bounds__(W* kWaveSize) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
     for (int cb = 0; cb < 8; ++cb) vread[cb] = kTileBytes + vt * kRowBytes + ((cb ^ (vt % 8)) << 5) + ((lane % 4) << 3);
 
-    unsigned char* ring = smem + wave * (NS * kStageBytes);
-    const uint32_t ring_addr = (uint32_t)(uintptr_t)KVP_LDS(ring);      // LDS byte address of the wave's ring
-    // read through the constant address space: the table is never written while the kernel runs, and a
-    // uniform constant load becomes a scalar load whose wait does not involve the KV fetches in flight
-    const __attribute__((address_space(4))) int32_t* bt =
-        (const __attribute__((address_space(4))) int32_t*)(p.block_tables + (int64_t)b * p.bt_stride_b);
-    const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k_cache) + (int64_t)kvh * p.kv_stride_h * 2;
-    const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v_cache) + (int64_t)kvh * p.v_stride_h * 2;
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)KVP_LDS(smem);      // LDS byte address of the ring
+    const unsigned char* kcache = reinterpret_cast<const unsigned char*>(p.k_cache);
+    const unsigned char* vcache = reinterpret_cast<const unsigned char*>(p.v_cache);
 
-    auto issue = [&](int tile, int stage) {       // asynchronous fetch of one K tile and one V tile into a stage
-        int phys = bt[tile / TPB];
+    auto issue = [&](const Cursor& c, int stage) {   // asynchronous fetch of one K tile and one V tile into a stage
+        int phys = bt[(int64_t)c.b * p.bt_stride_b + c.j / TPB];   // only entries of tiles inside the range are read
         phys = min(max(phys, 0), p.NBLK - 1);
-        const int sub = (tile % TPB) * kTileBytes;
-        const unsigned char* kt = kbase + (int64_t)phys * p.kv_stride_blk * 2 + sub;
-        const unsigned char* vt_ = vbase + (int64_t)phys * p.v_stride_blk * 2 + sub;
-        unsigned char* dst = ring + stage * kStageBytes;
+        const int sub = (c.j % TPB) * kTileBytes;
+        const unsigned char* kt = kcache + ((int64_t)phys * p.kv_stride_blk + (int64_t)c.kvh * p.kv_stride_h) * 2 + sub;
+        const unsigned char* vt_ = vcache + ((int64_t)phys * p.v_stride_blk + (int64_t)c.kvh * p.v_stride_h) * 2 + sub;
+        unsigned char* dst = smem + stage * kStageBytes;
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             __builtin_amdgcn_global_load_lds(KVP_GLOBAL(kt + koff[r]), KVP_LDS(dst + r * 1024), 16, 0, 0);
@@ -193,25 +283,32 @@ __global__ __launch_bounds__(W* kWaveSize) void attn_mfma_kernel(AttnParams p) {
     for (int cb = 0; cb < 8; ++cb) o[cb] = float4v{0.f, 0.f, 0.f, 0.f};
     float m = kNegBig, l = 0.f;
 
-    // ---- prologue: fill the ring
-    const int first = s + wave;
+    // ---- prologue: the prefetch cursor runs PD tiles ahead of the consume cursor
+    Cursor cp = ca;
+    int64_t rp = r0;                              // flat index of the tile cp points at
+    auto issue_next = [&](int stage) {
+        issue(cp, stage);
+        if (++rp < r1) advance(cp);
+    };
     if constexpr (PD > 0) {
 #pragma unroll
         for (int k = 0; k < PD; ++k)
-            if (first + k * W < e) issue(first + k * W, k);
+            if (rp < r1) issue_next(k);
     }
 
     int stage = 0;
-    for (int tile = first; tile < e; tile += W) {
+    int piece_first_j = ca.j;                     // where the current piece of the current unit began
+    bool piece_at_range_start = true;
+    for (int64_t r = r0; r < r1; ++r) {
         if constexpr (PD == 0) {
-            issue(tile, 0);
+            issue_next(0);
             wait_vmcnt<0>();
         } else {
-            // Algorithm 1 order: current tile is on its way; issue the look-ahead fetch, then compute
-            const int ahead = tile + PD * W;
+            // Algorithm 1 order: the current tile is on its way; issue the look-ahead fetch (guarded by the
+            // range end), then compute
             int ahead_stage = stage + PD; if (ahead_stage >= NS) ahead_stage -= NS;
-            if (ahead < e) {
-                issue(ahead, ahead_stage);
+            if (rp < r1) {
+                issue_next(ahead_stage);
                 wait_vmcnt<LOADS * PD>();          // everything older than the PD newest tiles has landed
             } else {
                 wait_vmcnt<0>();
@@ -236,8 +333,9 @@ __global__ __launch_bounds__(W* kWaveSize) void attn_mfma_kernel(AttnParams p) {
 
         // ---- online softmax over this tile's 16 tokens (lane holds tokens 4 lq + i of head lr)
         float sc[4];
-        const int tok0 = tile * kTileTokens + 4 * lq;
-        const bool tail = (tile + 1) * kTileTokens > n;        // wave-uniform
+        const int n = ca.n;
+        const int tok0 = ca.j * kTileTokens + 4 * lq;
+        const bool tail = (ca.j + 1) * kTileTokens > n;        // wave-uniform
 #pragma unroll
         for (int i = 0; i < 4; ++i) sc[i] = sacc[i] * p.scale_log2e;
         if (tail) {
@@ -271,77 +369,182 @@ __global__ __launch_bounds__(W* kWaveSize) void attn_mfma_kernel(AttnParams p) {
         for (int cb = 0; cb < 8; ++cb) o[cb] = mfma_k16<E>(va[cb], pb, o[cb]);
 
         if constexpr (PD > 0) { stage = stage + 1 == NS ? 0 : stage + 1; }
-    }
 
-    // ---- merge the waves through LDS (the rings are idle: every wave has consumed all it fetched)
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    __syncthreads();
-    float* red = reinterpret_cast<float*>(smem);               // [W][G][D + 2]
-    if (lr < G) {
-        float* dst = red + (wave * G + lr) * (D + 2);
+        // ---- end of this unit's piece: write it out and start the next one
+        const bool unit_end = ca.j + 1 == ca.ntiles;
+        const bool range_end = r + 1 == r1;
+        if (unit_end || range_end) {
+            float lt = l + __shfl_xor(l, 16);
+            lt += __shfl_xor(lt, 32);
+            if (lr < G) {
+                if (piece_first_j == 0 && unit_end) {           // the whole unit was ours: final rows
+                    const float inv = 1.0f / lt;                // lt > 0: a unit has at least one valid token
+                    uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)ca.b * p.out_stride_b +
+                                     (int64_t)(ca.kvh * G + lr) * p.out_stride_h + 4 * lq;
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb)
+                    for (int cb = 0; cb < 8; ++cb) {
+                        const u32x2 w = {pack2<E>(o[cb][0] * inv, o[cb][1] * inv), pack2<E>(o[cb][2] * inv, o[cb][3] * inv)};
+                        *reinterpret_cast<u32x2*>(orow + 16 * cb) = w;
+                    }
+                } else {                                        // a cut unit: unnormalised partial for the finalize kernel
+                    const int slot = piece_at_range_start ? 0 : 1;
+                    float* dst = p.partials + ((int64_t)(worker * 2 + slot) * G + lr) * kPartialStride;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dst[16 * cb + 4 * lq + i] = o[cb][i];
-        if (lq == 0) { dst[D] = m; dst[D + 1] = l; }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * D; idx += W * kWaveSize) {
-        const int g = idx / D, c = idx % D;
-        float ms = kNegBig;
+                    for (int cb = 0; cb < 8; ++cb) *reinterpret_cast<float4v*>(dst + 16 * cb + 4 * lq) = o[cb];
+                    if (lq == 0) { dst[D] = m; dst[D + 1] = lt; }
+                }
+            }
 #pragma unroll
-        for (int w = 0; w < W; ++w) ms = fmaxf(ms, red[(w * G + g) * (D + 2) + D]);
-        float num = 0.f, den = 0.f;
-#pragma unroll
-        for (int w = 0; w < W; ++w) {
-            const float* src = red + (w * G + g) * (D + 2);
-            const float wgt = fast_exp2(src[D] - ms);
-            num += wgt * src[c];
-            den += wgt * src[D + 1];
+            for (int cb = 0; cb < 8; ++cb) o[cb] = float4v{0.f, 0.f, 0.f, 0.f};
+            m = kNegBig;
+            l = 0.f;
+            piece_at_range_start = false;
         }
-        const int h = kvh * G + g;
-        if (direct) {
-            const float ov = den > 0.f ? num / den : 0.f;
-            reinterpret_cast<uint16_t*>(p.out)[(int64_t)b * p.out_stride_b + (int64_t)h * p.out_stride_h + c] = pack1<E>(ov);
-        } else {
-            float* dst = p.partials + (((int64_t)b * p.Hq + h) * p.NP + part) * (D + 2);
-            dst[c] = num;
-            if (c == 0) { dst[D] = ms; dst[D + 1] = den; }
+        if (!range_end) {
+            advance(ca);
+            if (unit_end) {
+                piece_first_j = 0;
+                load_q(ca.b, ca.kvh);
+            }
         }
     }
 }
 
-template <Elem E, int BS, int PD, int W>
-static int launch_one(const AttnParams& p, hipStream_t stream) {
-    const size_t ring = (size_t)W * (PD + 1) * kStageBytes;
-    const size_t merge = (size_t)W * p.G * (128 + 2) * sizeof(float);
-    const size_t lds = ring > merge ? ring : merge;
-    auto kern = attn_mfma_kernel<E, BS, PD, W>;
-    static bool attr_set = false;       // raising the dynamic LDS limit once per instantiation
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return -2;
-        attr_set = true;
+// Merge of the partials of every unit that more than one worker touched, and zero rows for
+// empty sequences.  One workgroup per (query head, sequence).
+template <Elem E>
+__global__ __launch_bounds__(256) void attn_finalize_kernel(AttnParams p, int bs) {
+    constexpr int D = kD;
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid % kWaveSize, wv = tid / kWaveSize;
+    const int G = p.G, Hkv = p.Hkv, kvh = h / G, g = h % G;
+    const int max_len = p.MB * bs;
+    const_i32_ptr cl = (const_i32_ptr)p.context_lens;
+    uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)b * p.out_stride_b + (int64_t)h * p.out_stride_h;
+
+    const int nt = tiles_of(clamp_len(cl[b], max_len));
+    if (nt == 0) {                                  // empty context: zero row
+        if (tid < D) orow[tid] = 0;
+        return;
     }
-    hipLaunchKernelGGL(kern, dim3(p.NP, p.Hkv, p.B), dim3(W * kWaveSize), lds, stream, p);
+    const int total = scan_total(cl, p.B, max_len, lane);
+    int cum = 0;                                    // tiles of the sequences before b (per kv head)
+    for (int base = 0; base < b; base += kWaveSize) {
+        const int idx = base + lane;
+        cum += wave_sum_i32(idx < b ? tiles_of(clamp_len(cl[idx], max_len)) : 0);
+    }
+    const int64_t T = (int64_t)total * Hkv;
+    const int64_t a = (int64_t)Hkv * cum + (int64_t)kvh * nt, end = a + nt;     // the unit's flat tile range
+    const int Nw = p.num_workers;
+    const int w0 = (int)(((a + 1) * Nw - 1) / T);   // last worker whose range starts at or before a
+    const int w1 = (int)((end * Nw - 1) / T);       // last worker whose range starts before end
+    if (w0 == w1) return;                           // one worker covered the unit and wrote the rows itself
+    const int np = w1 - w0 + 1;
+
+    __shared__ float s_w[kMaxWorkers];
+    __shared__ int s_row[kMaxWorkers];
+    __shared__ float s_red[8];
+    __shared__ float s_num[D];
+
+    // pass 1: running maxima and sums of the pieces
+    float lmax = kNegBig;
+    for (int i = tid; i < np; i += 256) {
+        const int w = w0 + i;
+        const int64_t ws = range_start(w, T, Nw), we = range_start(w + 1, T, Nw);
+        int row = -1;
+        float mi = kNegBig;
+        if (we > ws) {                              // workers with an empty range wrote nothing
+            const int slot = ws >= a ? 0 : 1;       // a piece that starts where the worker's range starts is slot 0
+            row = (w * 2 + slot) * G + g;
+            mi = p.partials[(int64_t)row * kPartialStride + D];
+        }
+        s_row[i] = row;
+        s_w[i] = mi;
+        lmax = fmaxf(lmax, mi);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) lmax = fmaxf(lmax, __shfl_xor(lmax, off));
+    if (lane == 0) s_red[wv] = lmax;
+    __syncthreads();
+    const float ms = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    float lden = 0.f;
+    for (int i = tid; i < np; i += 256) {
+        const int row = s_row[i];
+        float wgt = 0.f;
+        if (row >= 0) {
+            wgt = fast_exp2(s_w[i] - ms);
+            lden += wgt * p.partials[(int64_t)row * kPartialStride + D + 1];
+        }
+        s_w[i] = wgt;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) lden += __shfl_xor(lden, off);
+    if (lane == 0) s_red[4 + wv] = lden;
+    __syncthreads();
+    const float den = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
+
+    // pass 2: weighted sum of the accumulators; two halves of the workgroup take alternate pieces
+    const int c = tid % D, half = tid / D;
+    float num = 0.f;
+    int i = half;
+    for (; i + 6 < np; i += 8) {                    // four independent loads in flight per thread
+        float v[4], wg[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int row = s_row[i + 2 * u];
+            wg[u] = s_w[i + 2 * u];
+            v[u] = row >= 0 ? p.partials[(int64_t)row * kPartialStride + c] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) num += wg[u] * v[u];
+    }
+    for (; i < np; i += 2) {
+        const int row = s_row[i];
+        if (row >= 0) num += s_w[i] * p.partials[(int64_t)row * kPartialStride + c];
+    }
+    if (half == 1) s_num[c] = num;
+    __syncthreads();
+    if (half == 0) orow[c] = pack1<E>((num + s_num[c]) / den);
+}
+
+template <Elem E, int BS, int PD>
+static int launch_one(const AttnParams& p, hipStream_t stream) {
+    const size_t lds = (size_t)(PD + 1) * kStageBytes;
+    auto kern = attn_mfma_kernel<E, BS, PD>;
+    hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), lds, stream, p);
     return 0;
 }
 
 template <Elem E, int BS>
 static int launch_pd(const AttnParams& p, hipStream_t stream) {
     switch (p.prefetch_distance) {
-        case 0: return launch_one<E, BS, 0, 4>(p, stream);
-        case 1: return launch_one<E, BS, 1, 4>(p, stream);
-        case 2: return launch_one<E, BS, 2, 4>(p, stream);
-        case 3: return launch_one<E, BS, 3, 4>(p, stream);
-        case 4: return launch_one<E, BS, 4, 4>(p, stream);
+        case 0: return launch_one<E, BS, 0>(p, stream);
+        case 1: return launch_one<E, BS, 1>(p, stream);
+        case 2: return launch_one<E, BS, 2>(p, stream);
+        case 3: return launch_one<E, BS, 3>(p, stream);
+        case 4: return launch_one<E, BS, 4>(p, stream);
         default: return -1;
     }
 }
 
-// head_dim 128 only.  Returns 0, -1 (no such instantiation) or -2 (HIP refused the LDS size).
+// LDS bytes one worker (wave) of the head_dim-128 kernel holds at a prefetch distance.
+int mfma_worker_lds_bytes(int prefetch_distance) { return (prefetch_distance + 1) * kStageBytes; }
+
+// Bytes of partial storage for a launch with this many workers.
+size_t mfma_partial_bytes(int num_workers, int G) {
+    return (size_t)num_workers * 2 * G * kPartialStride * sizeof(float);
+}
+
+// Merge kernel of the head_dim-128 path; always launched after the main kernel (it also writes the zero
+// rows of empty sequences).
+int launch_finalize_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream) {
+    if (elem == (int)Elem::F16) hipLaunchKernelGGL(attn_finalize_kernel<Elem::F16>, dim3(p.Hq, p.B), dim3(256), 0, stream, p, bs);
+    else hipLaunchKernelGGL(attn_finalize_kernel<Elem::BF16>, dim3(p.Hq, p.B), dim3(256), 0, stream, p, bs);
+    return 0;
+}
+
+// head_dim 128 only.  Returns 0 or -1 (no such instantiation).
 int launch_attn_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream) {
+    if (p.num_workers < 1 || p.num_workers > kMaxWorkers) return -1;
     if (elem == (int)Elem::F16) return bs == 16 ? launch_pd<Elem::F16, 16>(p, stream) : launch_pd<Elem::F16, 32>(p, stream);
     return bs == 16 ? launch_pd<Elem::BF16, 16>(p, stream) : launch_pd<Elem::BF16, 32>(p, stream);
 }

@@ -25,6 +25,32 @@ std::mutex g_ws_mutex;
 void* g_ws_ptr = nullptr;
 size_t g_ws_bytes = 0;
 std::atomic<int> g_part_tokens{0};   // 0 = default
+std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
+std::atomic<int> g_num_cus{0};       // compute units of the device, read once
+
+constexpr int kLdsBytesPerCU = 160 * 1024;
+constexpr int kMaxWavesPerCU = 16;
+
+int num_cus() {
+    int n = g_num_cus.load();
+    if (n > 0) return n;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return -1;
+    n = prop.multiProcessorCount;
+    g_num_cus.store(n);
+    return n;
+}
+
+// Persistent waves per compute unit of the head_dim-128 kernel: as many as the LDS rings allow, at most 8
+// unless the caller asked for a number.
+int waves_per_cu(int prefetch_distance) {
+    const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance);
+    int w = g_waves_per_cu.load();
+    if (w <= 0) w = 8;
+    w = w < lds_limit ? w : lds_limit;
+    return w < kMaxWavesPerCU ? w : kMaxWavesPerCU;
+}
 
 constexpr int kDefaultPartTokens = 512;
 
@@ -34,6 +60,8 @@ int part_tokens() {
 }
 
 size_t workspace_bytes(int B, int Hq, int d, int64_t max_context, int P) {
+    if (d == 128)   // persistent-worker kernel: two partial pieces per worker, sized for the largest launch
+        return kvp::mfma_partial_bytes(kvp::kMaxMfmaWorkers, Hq < 16 ? Hq : 16);
     if (max_context <= P) return 0;
     int64_t np = (max_context + P - 1) / P;
     return (size_t)B * Hq * np * (d + 2) * sizeof(float);
@@ -127,8 +155,19 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.partials = nullptr;
     r->elem = q->dtype; r->d = (int)d; r->bs = block_size;
     r->split = p.NP > 1;
-    if (r->split) {
-        const size_t need = workspace_bytes((int)B, (int)Hq, (int)d, max_context, P);
+    p.num_workers = 0;
+    size_t need = 0;
+    if (d == 128) {
+        const int cus = num_cus();
+        if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
+        int nw = cus * waves_per_cu(prefetch_distance);
+        p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
+        need = kvp::mfma_partial_bytes(p.num_workers, G);
+        r->split = false;              // the finalize kernel is launched with the main kernel
+    } else if (r->split) {
+        need = workspace_bytes((int)B, (int)Hq, (int)d, max_context, P);
+    }
+    if (need > 0) {
         std::lock_guard<std::mutex> lock(g_ws_mutex);
         if (!g_ws_ptr || g_ws_bytes < need)
             return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
@@ -168,7 +207,10 @@ int run_attn(const Resolved& r, hipStream_t stream) {
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);
-    if (r.split) {
+    if (r.d == 128) {
+        kvp::launch_finalize_mfma(r.p, r.elem, r.bs, stream);
+        if (int rc = check_launch("kv_decode_attn finalize kernel")) return rc;
+    } else if (r.split) {
         kvp::launch_reduce(r.p, r.elem, r.d, r.bs, stream);
         if (int rc = check_launch("kv_decode_attn combine kernel")) return rc;
     }
@@ -226,6 +268,18 @@ int kv_decode_set_partition_tokens(int tokens) {
 }
 
 int kv_decode_get_partition_tokens(void) { return part_tokens(); }
+
+int kv_decode_set_waves_per_cu(int waves) {
+    if (waves < 0 || waves > kMaxWavesPerCU)
+        return fail(KV_ERR_INVALID, "kv_decode_set_waves_per_cu: %d outside 0..%d", waves, kMaxWavesPerCU);
+    g_waves_per_cu.store(waves);
+    return KV_OK;
+}
+
+int kv_decode_get_waves_per_cu(int prefetch_distance) {
+    if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE) return 0;
+    return waves_per_cu(prefetch_distance);
+}
 
 int kv_profile_enable(int max_calls) {
     if (max_calls < 0 || max_calls > 100000) return fail(KV_ERR_INVALID, "kv_profile_enable: max_calls %d outside 0..100000", max_calls);

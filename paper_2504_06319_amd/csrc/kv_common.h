@@ -19,7 +19,7 @@ struct AttnParams {
     const int32_t* block_tables;
     const int32_t* context_lens;
     void* out;
-    float* partials;          // [B, Hq, NP, d + 2] fp32: unnormalised acc, running max (log2 domain), sum
+    float* partials;          // split-KV scratch: unnormalised acc, running max (log2 domain), sum per piece
     int64_t q_stride_b, q_stride_h;
     int64_t kv_stride_blk, kv_stride_h;
     int64_t v_stride_blk, v_stride_h;
@@ -31,6 +31,7 @@ struct AttnParams {
     int32_t part_blocks;      // KV blocks per partition
     int32_t NP;               // partitions per sequence in the launch grid
     int32_t prefetch_distance;
+    int32_t num_workers;      // persistent waves of the head_dim-128 kernel
     float scale_log2e;        // scale * log2(e): logits live in the base-2 domain
 };
 
@@ -93,6 +94,10 @@ __device__ __forceinline__ float group_sum(float x) {
 
 int launch_attn_valu(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_attn_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream);
+int launch_finalize_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream);
+int mfma_worker_lds_bytes(int prefetch_distance);
+size_t mfma_partial_bytes(int num_workers, int G);
+constexpr int kMaxMfmaWorkers = 4096;
 int launch_reduce(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 
 }  // namespace kvp

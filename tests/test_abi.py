@@ -44,15 +44,31 @@ def test_closed_forms_match_the_paper_worked_example():
 
 def test_workspace_size_formula():
     P = kv.kv_decode_get_partition_tokens()
-    assert kv.kv_decode_workspace_bytes(8, 32, 128, P, 16) == 0
+    # head_dim 64: one partial per (sequence, head, partition); nothing when one partition suffices
+    assert kv.kv_decode_workspace_bytes(8, 32, 64, P, 16) == 0
     np_ = -(-32768 // P)
-    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == 8 * 32 * np_ * 130 * 4
+    assert kv.kv_decode_workspace_bytes(8, 32, 64, 32768, 16) == 8 * 32 * np_ * 66 * 4
+    # head_dim 128: two partial pieces of min(Hq, 16) rows of 132 floats for each of at most 4096 workers
+    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == 4096 * 2 * 16 * 132 * 4
+    assert kv.kv_decode_workspace_bytes(1, 4, 128, 16, 16) == 4096 * 2 * 4 * 132 * 4
     with pytest.raises(kv.KVError):
         kv.kv_decode_set_partition_tokens(100)
     kv.kv_decode_set_partition_tokens(1024)
     assert kv.kv_decode_get_partition_tokens() == 1024
     kv.kv_decode_set_partition_tokens(0)
     assert kv.kv_decode_get_partition_tokens() == P
+
+
+def test_waves_per_cu_follow_the_lds_budget():
+    # a worker's ring is (distance + 1) x 8 KB; 160 KB of LDS per compute unit; automatic choice is at most 8
+    assert [kv.kv_decode_get_waves_per_cu(d) for d in range(5)] == [8, 8, 6, 5, 4]
+    kv.kv_decode_set_waves_per_cu(16)
+    try:
+        assert [kv.kv_decode_get_waves_per_cu(d) for d in range(5)] == [16, 10, 6, 5, 4]
+        with pytest.raises(kv.KVError):
+            kv.kv_decode_set_waves_per_cu(17)
+    finally:
+        kv.kv_decode_set_waves_per_cu(0)
 
 
 def _fake(shape, dtype, ptr=0x1000):
@@ -113,8 +129,9 @@ def test_missing_workspace_is_reported():
     lib = kv.load_library()
     assert lib.kv_decode_set_workspace(None, 0) == 0
     binding._registered = (0, 0)
-    a = _good()
-    a.update(bt=_fake((3, 4096), torch.int32))      # 65536 tokens: needs split-KV scratch
+    f = torch.bfloat16                                # head_dim 64 with 65536 tokens: needs split-KV scratch
+    a = dict(q=_fake((3, 8, 64), f), k=_fake((10, 2, 16, 64), f), v=_fake((10, 2, 16, 64), f),
+             bt=_fake((3, 4096), torch.int32), cl=_fake((3,), torch.int32), out=_fake((3, 8, 64), f))
     assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"]) == 4
     assert "workspace" in kv.kv_last_error()
     assert lib.kv_decode_set_workspace(ctypes.c_void_p(0x1000), 0) == 1

@@ -40,8 +40,12 @@ def test_shapes_groups_and_dtypes(dtype, d, bs, G):
 @pytest.mark.parametrize("pd", list(range(0, kv.KV_MAX_PREFETCH_DISTANCE + 1)))
 def test_every_prefetch_distance_gives_the_same_result(pd):
     c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 7, DEV, poison=True, lens=[3000, 17, 2049, 1024])
-    ref = run_hip(c, 0)
-    got = run_hip(c, pd)
+    kv.kv_decode_set_waves_per_cu(4)       # same worker count, hence the same cuts, at every distance
+    try:
+        ref = run_hip(c, 0)
+        got = run_hip(c, pd)
+    finally:
+        kv.kv_decode_set_waves_per_cu(0)
     compare(got, run_oracle(c), f"pd={pd}")
     assert torch.equal(got, ref), "prefetching must not change any value"
 
@@ -59,12 +63,44 @@ def test_split_kv_partitions_and_combine():
 
 @pytest.mark.parametrize("P", [128, 256, 2048])
 def test_other_partition_sizes(P):
+    """head_dim 64 path: partition size of the split-KV grid."""
     kv.kv_decode_set_partition_tokens(P)
     try:
-        c = synth.make_case(_cfg(4, 1, 128, 32, "bf16"), 13, DEV, poison=True, lens=[P + 5, 4 * P, 77, 6 * P + 1])
+        c = synth.make_case(_cfg(4, 1, 64, 32, "bf16"), 13, DEV, poison=True, lens=[P + 5, 4 * P, 77, 6 * P + 1])
         check_case(c, 2, f"P={P}")
     finally:
         kv.kv_decode_set_partition_tokens(0)
+
+
+@pytest.mark.parametrize("waves", [1, 3, 8, 16])
+@pytest.mark.parametrize("pd", [0, 1, 4])
+def test_other_worker_counts_cut_units_differently(waves, pd):
+    """head_dim 128 path: the number of persistent workers decides where units are cut into pieces;
+    every cut must give the same result.  One long sequence spans hundreds of workers, short
+    ones are covered whole, empty ones get zero rows."""
+    kv.kv_decode_set_waves_per_cu(waves)
+    try:
+        lens = [40000, 0, 5, 16, 17, 3000, 0, 1, 12345, 640, 0]
+        c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 43 + waves, DEV, poison=True, lens=lens)
+        got = run_hip(c, pd)
+        compare(got, run_oracle(c), f"waves={waves} pd={pd}")
+        for b, n in enumerate(lens):
+            if n == 0:
+                assert (got[b] == 0).all()
+    finally:
+        kv.kv_decode_set_waves_per_cu(0)
+
+
+def test_single_unit_spanning_every_worker():
+    c = synth.make_case(_cfg(4, 1, 128, 32, "f16"), 47, DEV, poison=True, lens=[70001])
+    check_case(c, 2, "one unit")
+
+
+def test_more_sequences_than_lanes_in_the_length_scan():
+    rng = np.random.default_rng(5)
+    lens = rng.integers(0, 200, 300).tolist()
+    c = synth.make_case(_cfg(4, 2, 128, 16, "bf16"), 53, DEV, poison=True, lens=lens)
+    check_case(c, 1, "300 sequences")
 
 
 def test_empty_and_single_token_contexts():
@@ -150,7 +186,7 @@ def test_full_size_configuration_on_sampled_rows(index):
     c = synth.make_case(cfg, synth.config_seed(index), DEV)
     got0 = run_hip(c, 0)
     got1 = run_hip(c, 2)
-    assert torch.equal(got0, got1)
+    assert (got0.float() - got1.float()).abs().max() <= 2e-2    # different worker counts cut units differently
     rng = np.random.default_rng(index)
     lens = c["lens"]
     seqs = {int(np.argmin(lens)), int(np.argmax(lens))} | set(rng.integers(0, cfg["B"], 6).tolist())
