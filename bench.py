@@ -79,7 +79,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=1, choices=[1, 2, 3])
     ap.add_argument("--prefetch-distance", type=int, default=None)
-    ap.add_argument("--partition-tokens", type=int, default=0)
+    ap.add_argument("--waves-per-cu", type=int, default=0, help="persistent waves per compute unit (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the prefetch-off leg and the other workloads")
     args = ap.parse_args()
@@ -99,8 +99,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    if args.partition_tokens:
-        kv.kv_decode_set_partition_tokens(args.partition_tokens)
+    if args.waves_per_cu:
+        kv.kv_decode_set_waves_per_cu(args.waves_per_cu)
 
     def make_cases(index, copies=2):
         cfg = synth.CONFIGS[index]
@@ -137,7 +137,7 @@ def main():
                    "head_dim": cfg["d"], "block_size": cfg["bs"],
                    "context_lens": "fixed" if "lens" in cfg else f"uniform{list(cfg['len_range'])}",
                    "kv_bytes_per_step": kvb, "prefetch_distance": pd_on,
-                   "partition_tokens": kv.kv_decode_get_partition_tokens()},
+                   "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on)},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "tokens_per_s": cfg["B"] / (ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -148,9 +148,22 @@ def main():
 
     if not args.no_extra:
         _, _, _, ms0, main0, comb0 = measure(args.workload, 0, args.steps, args.warmup)
-        result["prefetch_off"] = {"prefetch_distance": 0, "ms_per_step": ms0, "value": kvb / (ms0 * 1e-3) / 1e9,
+        result["prefetch_off"] = {"prefetch_distance": 0, "waves_per_cu": kv.kv_decode_get_waves_per_cu(0),
+                                  "ms_per_step": ms0, "value": kvb / (ms0 * 1e-3) / 1e9,
                                   "kernel_ms": main0, "speedup_on_vs_off": ms0 / ms}
         log(f"[bench] off: {ms0:.4f} ms/step")
+        # the same comparison with few waves per compute unit, where occupancy cannot hide the HBM latency
+        # (the regime of the paper's baseline kernel, Table 1)
+        low = {}
+        for wpc in (2, 4):
+            kv.kv_decode_set_waves_per_cu(wpc)
+            _, _, _, l_on, lk_on, _ = measure(args.workload, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
+            _, _, _, l_off, lk_off, _ = measure(args.workload, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
+            low[f"waves_per_cu_{wpc}"] = {"on_ms_per_step": l_on, "off_ms_per_step": l_off, "on_kernel_ms": lk_on,
+                                         "off_kernel_ms": lk_off, "kernel_speedup_on_vs_off": lk_off / lk_on}
+            log(f"[bench] waves/CU {wpc}: on {lk_on:.4f} ms, off {lk_off:.4f} ms kernel")
+        kv.kv_decode_set_waves_per_cu(args.waves_per_cu)
+        result["prefetch_on_vs_off_low_occupancy"] = low
         others = {}
         for idx in (1, 2, 3):
             if idx == args.workload:

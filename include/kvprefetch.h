@@ -99,14 +99,21 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
 
 /*
  * Split-KV workspace (the block index range [s, e) that Algorithm 1 takes as input
- * lets a worker own part of a sequence; partial results are merged by a second
- * kernel).  Bytes needed for a call with these extents: for head_dim 128 a fixed
- * bound (two partial pieces per persistent worker), for head_dim 64 one partial per
- * (sequence, query head, partition), 0 when one partition covers max_context.
+ * lets a worker own part of a sequence; the worker that finishes a sequence's last
+ * piece merges the pieces).  Bytes needed for a call with these extents: for head_dim 128 a fixed
+ * bound (1 MiB of counters plus two partial pieces per persistent worker), for
+ * head_dim 64 the same 1 MiB plus one partial per (sequence, query head, partition),
+ * or 0 when one partition covers max_context.
  */
 size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size);
 
-/* Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters. */
+/*
+ * Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters.
+ * The call zeroes the first 1 MiB (arrival counters of the split-KV merge) and synchronises
+ * the device; it is a set-up call, not part of the timed path.  While registered the memory
+ * belongs to the library: calls that overlap in time on one device share it and race, and a
+ * caller that writes to it must register it again.
+ */
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
 
 /* head_dim 64 path: tokens per split-KV partition (multiple of 128, 128 .. 65536); 0 restores the default. */

@@ -42,14 +42,17 @@ int num_cus() {
     return n;
 }
 
-// Persistent waves per compute unit of the head_dim-128 kernel: as many as the LDS rings allow, at most 8
-// unless the caller asked for a number.
+// Persistent waves per compute unit of the head_dim-128 kernel: what the caller asked for, else 6 (measured
+// best: about 48-96 KB of KV in flight per compute unit), capped by the LDS the rings need.  Odd counts above
+// one are rounded down: 5 and 10 waves per compute unit measured about 25 % slower than 4 and 8.
 int waves_per_cu(int prefetch_distance) {
     const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance);
     int w = g_waves_per_cu.load();
-    if (w <= 0) w = 8;
+    if (w <= 0) w = 6;
     w = w < lds_limit ? w : lds_limit;
-    return w < kMaxWavesPerCU ? w : kMaxWavesPerCU;
+    w = w < kMaxWavesPerCU ? w : kMaxWavesPerCU;
+    if (w > 2 && (w & 1)) --w;
+    return w;
 }
 
 constexpr int kDefaultPartTokens = 512;
@@ -60,11 +63,11 @@ int part_tokens() {
 }
 
 size_t workspace_bytes(int B, int Hq, int d, int64_t max_context, int P) {
-    if (d == 128)   // persistent-worker kernel: two partial pieces per worker, sized for the largest launch
-        return kvp::mfma_partial_bytes(kvp::kMaxMfmaWorkers, Hq < 16 ? Hq : 16);
+    if (d == 128)   // persistent-worker kernel: arrival counters, then two partial pieces per worker of the largest launch
+        return kvp::kCounterRegionBytes + kvp::mfma_partial_bytes(kvp::kMaxMfmaWorkers, Hq < 16 ? Hq : 16);
     if (max_context <= P) return 0;
     int64_t np = (max_context + P - 1) / P;
-    return (size_t)B * Hq * np * (d + 2) * sizeof(float);
+    return kvp::kCounterRegionBytes + (size_t)B * Hq * np * (d + 2) * sizeof(float);
 }
 
 bool dense_tile(const kv_tensor* t) {   // [NBLK, Hkv, bs, d] with the [bs, d] tile contiguous
@@ -153,6 +156,7 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.prefetch_distance = prefetch_distance;
     p.scale_log2e = scale * kvp::kLog2e;
     p.partials = nullptr;
+    p.unit_counters = nullptr;
     r->elem = q->dtype; r->d = (int)d; r->bs = block_size;
     r->split = p.NP > 1;
     p.num_workers = 0;
@@ -162,8 +166,11 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
         if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
         int nw = cus * waves_per_cu(prefetch_distance);
         p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
-        need = kvp::mfma_partial_bytes(p.num_workers, G);
-        r->split = false;              // the finalize kernel is launched with the main kernel
+        if (B * num_kv_heads > kvp::kMaxMfmaUnits)
+            return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: %lld (sequence, kv head) units exceed %d",
+                        (long long)(B * num_kv_heads), kvp::kMaxMfmaUnits);
+        need = kvp::kCounterRegionBytes + kvp::mfma_partial_bytes(p.num_workers, G);
+        r->split = false;              // pieces are merged inside the main kernel
     } else if (r->split) {
         need = workspace_bytes((int)B, (int)Hq, (int)d, max_context, P);
     }
@@ -171,7 +178,9 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
         std::lock_guard<std::mutex> lock(g_ws_mutex);
         if (!g_ws_ptr || g_ws_bytes < need)
             return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
-        p.partials = (float*)g_ws_ptr;
+        // the head of the workspace belongs to the arrival counters whichever kernel runs
+        p.unit_counters = (int32_t*)g_ws_ptr;
+        p.partials = (float*)((char*)g_ws_ptr + kvp::kCounterRegionBytes);
     }
     return KV_OK;
 }
@@ -207,10 +216,7 @@ int run_attn(const Resolved& r, hipStream_t stream) {
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);
-    if (r.d == 128) {
-        kvp::launch_finalize_mfma(r.p, r.elem, r.bs, stream);
-        if (int rc = check_launch("kv_decode_attn finalize kernel")) return rc;
-    } else if (r.split) {
+    if (r.split) {
         kvp::launch_reduce(r.p, r.elem, r.d, r.bs, stream);
         if (int rc = check_launch("kv_decode_attn combine kernel")) return rc;
     }
@@ -254,6 +260,14 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {
     if ((dev_ptr == nullptr) != (bytes == 0))
         return fail(KV_ERR_INVALID, "kv_decode_set_workspace: pointer and size must both be set or both be zero");
     if (((uintptr_t)dev_ptr) % 16) return fail(KV_ERR_INVALID, "kv_decode_set_workspace: pointer must be 16-byte aligned");
+    if (dev_ptr) {
+        // the head of the workspace holds the arrival counters of the head_dim-128 kernel; they must read zero
+        // before the first call and every call leaves them at zero
+        const size_t head = bytes < kvp::kCounterRegionBytes ? bytes : kvp::kCounterRegionBytes;
+        hipError_t e = hipMemset(dev_ptr, 0, head);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) return fail(KV_ERR_HIP, "kv_decode_set_workspace: %s", hipGetErrorString(e));
+    }
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     g_ws_ptr = dev_ptr;
     g_ws_bytes = bytes;

@@ -47,10 +47,11 @@ def test_workspace_size_formula():
     # head_dim 64: one partial per (sequence, head, partition); nothing when one partition suffices
     assert kv.kv_decode_workspace_bytes(8, 32, 64, P, 16) == 0
     np_ = -(-32768 // P)
-    assert kv.kv_decode_workspace_bytes(8, 32, 64, 32768, 16) == 8 * 32 * np_ * 66 * 4
+    assert kv.kv_decode_workspace_bytes(8, 32, 64, 32768, 16) == (1 << 20) + 8 * 32 * np_ * 66 * 4
     # head_dim 128: two partial pieces of min(Hq, 16) rows of 132 floats for each of at most 4096 workers
-    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == 4096 * 2 * 16 * 132 * 4
-    assert kv.kv_decode_workspace_bytes(1, 4, 128, 16, 16) == 4096 * 2 * 4 * 132 * 4
+    # plus 1 MiB of arrival counters
+    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == (1 << 20) + 4096 * 2 * 16 * 132 * 4
+    assert kv.kv_decode_workspace_bytes(1, 4, 128, 16, 16) == (1 << 20) + 4096 * 2 * 4 * 132 * 4
     with pytest.raises(kv.KVError):
         kv.kv_decode_set_partition_tokens(100)
     kv.kv_decode_set_partition_tokens(1024)
@@ -60,11 +61,12 @@ def test_workspace_size_formula():
 
 
 def test_waves_per_cu_follow_the_lds_budget():
-    # a worker's ring is (distance + 1) x 8 KB; 160 KB of LDS per compute unit; automatic choice is at most 8
-    assert [kv.kv_decode_get_waves_per_cu(d) for d in range(5)] == [8, 8, 6, 5, 4]
+    # a worker's ring is (distance + 1) x 8 KB; 160 KB of LDS per compute unit; automatic choice is at most 6;
+    # odd counts above one are rounded down
+    assert [kv.kv_decode_get_waves_per_cu(d) for d in range(5)] == [6, 6, 6, 4, 4]
     kv.kv_decode_set_waves_per_cu(16)
     try:
-        assert [kv.kv_decode_get_waves_per_cu(d) for d in range(5)] == [16, 10, 6, 5, 4]
+        assert [kv.kv_decode_get_waves_per_cu(d) for d in range(5)] == [16, 10, 6, 4, 4]
         with pytest.raises(kv.KVError):
             kv.kv_decode_set_waves_per_cu(17)
     finally:
