@@ -25,7 +25,7 @@ def log(msg):
 
 def timed_steps(kv, torch, cases, pd, steps, warmup):
     """W untimed + K timed steps, alternating between the cache copies.  Returns
-    (ms per step by wall clock, main-kernel ms per launch and combine ms per launch by HIP events)."""
+    (ms per step by wall clock, main-kernel ms per launch by HIP events on the launch stream)."""
     def step(i):
         c = cases[i % len(cases)]
         kv.kv_decode_attn(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], c["out"],
@@ -39,10 +39,10 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    main_ms, comb_ms, n = kv.kv_profile_read()
+    main_ms, n = kv.kv_profile_read()
     kv.kv_profile_enable(0)
     assert n == steps
-    return (t1 - t0) * 1e3 / steps, main_ms / n, comb_ms / n
+    return (t1 - t0) * 1e3 / steps, main_ms / n
 
 
 def cpu_baseline(oracle, synth, case, cfg, budget_s=20.0):
@@ -115,12 +115,12 @@ def main():
     def measure(index, pd, steps, warmup):
         cfg, cases = make_cases(index)
         kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"])
-        ms, main_ms, comb_ms = timed_steps(kv, torch, cases, pd, steps, warmup)
-        return cfg, cases, kvb, ms, main_ms, comb_ms
+        ms, main_ms = timed_steps(kv, torch, cases, pd, steps, warmup)
+        return cfg, cases, kvb, ms, main_ms
 
     pd_on = args.prefetch_distance if args.prefetch_distance is not None else 2
     log(f"[bench] workload {args.workload} prefetch_distance {pd_on}")
-    cfg, cases, kvb, ms, main_ms, comb_ms = measure(args.workload, pd_on, args.steps, args.warmup)
+    cfg, cases, kvb, ms, main_ms = measure(args.workload, pd_on, args.steps, args.warmup)
     value = kvb / (ms * 1e-3) / 1e9
     achieved = kvb / (main_ms * 1e-3) / 1e9
     traffic = None
@@ -142,12 +142,13 @@ def main():
         "tokens_per_s": cfg["B"] / (ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "main attention kernel", "kernel_ms": main_ms, "combine_ms": comb_ms},
+                     "kernel": "attn_mfma_kernel (main attention kernel)", "kernel_ms": main_ms,
+                     "algorithmic_bytes_per_launch": kvb},
     }
-    log(f"[bench] on: {ms:.4f} ms/step, {value:.0f} GB/s; main kernel {main_ms:.4f} ms, combine {comb_ms:.4f} ms")
+    log(f"[bench] on: {ms:.4f} ms/step, {value:.0f} GB/s; main kernel {main_ms:.4f} ms")
 
     if not args.no_extra:
-        _, _, _, ms0, main0, comb0 = measure(args.workload, 0, args.steps, args.warmup)
+        _, _, _, ms0, main0 = measure(args.workload, 0, args.steps, args.warmup)
         result["prefetch_off"] = {"prefetch_distance": 0, "waves_per_cu": kv.kv_decode_get_waves_per_cu(0),
                                   "ms_per_step": ms0, "value": kvb / (ms0 * 1e-3) / 1e9,
                                   "kernel_ms": main0, "speedup_on_vs_off": ms0 / ms}
@@ -157,8 +158,8 @@ def main():
         low = {}
         for wpc in (2, 4):
             kv.kv_decode_set_waves_per_cu(wpc)
-            _, _, _, l_on, lk_on, _ = measure(args.workload, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
-            _, _, _, l_off, lk_off, _ = measure(args.workload, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
+            _, _, _, l_on, lk_on = measure(args.workload, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
+            _, _, _, l_off, lk_off = measure(args.workload, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
             low[f"waves_per_cu_{wpc}"] = {"on_ms_per_step": l_on, "off_ms_per_step": l_off, "on_kernel_ms": lk_on,
                                          "off_kernel_ms": lk_off, "kernel_speedup_on_vs_off": lk_off / lk_on}
             log(f"[bench] waves/CU {wpc}: on {lk_on:.4f} ms, off {lk_off:.4f} ms kernel")
@@ -169,8 +170,8 @@ def main():
             if idx == args.workload:
                 continue
             torch.cuda.empty_cache()
-            ocfg, _, okvb, oms, omain, _ = measure(idx, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
-            _, _, _, oms0, _, _ = measure(idx, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
+            ocfg, _, okvb, oms, omain = measure(idx, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
+            _, _, _, oms0, _ = measure(idx, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
             others[ocfg["name"]] = {"value": okvb / (oms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_step": oms,
                                     "pct_hbm_peak": 100.0 * okvb / (oms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                     "kernel_ms": omain, "prefetch_off_ms_per_step": oms0,

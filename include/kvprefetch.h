@@ -99,21 +99,14 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
 
 /*
  * Split-KV workspace (the block index range [s, e) that Algorithm 1 takes as input
- * lets a worker own part of a sequence; the worker that finishes a sequence's last
- * piece merges the pieces).  Bytes needed for a call with these extents: for head_dim 128 a fixed
- * bound (1 MiB of counters plus two partial pieces per persistent worker), for
- * head_dim 64 the same 1 MiB plus one partial per (sequence, query head, partition),
- * or 0 when one partition covers max_context.
+ * lets a worker own part of a sequence; partial results are merged by a second
+ * kernel).  Bytes needed for a call with these extents: for head_dim 128 a fixed
+ * bound (two partial pieces per persistent worker), for head_dim 64 one partial per
+ * (sequence, query head, partition), 0 when one partition covers max_context.
  */
 size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size);
 
-/*
- * Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters.
- * The call zeroes the first 1 MiB (arrival counters of the split-KV merge) and synchronises
- * the device; it is a set-up call, not part of the timed path.  While registered the memory
- * belongs to the library: calls that overlap in time on one device share it and race, and a
- * caller that writes to it must register it again.
- */
+/* Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters. */
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
 
 /* head_dim 64 path: tokens per split-KV partition (multiple of 128, 128 .. 65536); 0 restores the default. */
@@ -131,17 +124,16 @@ int kv_decode_set_waves_per_cu(int waves);
 int kv_decode_get_waves_per_cu(int prefetch_distance);
 
 /*
- * Per-kernel timing with HIP events on the call's own stream (the paper reports the
- * attention kernel's duration, Table 2).  kv_profile_enable(n) creates events for the
- * next n kv_decode_attn calls (host-side allocation, not on the timed path;
- * n = 0 frees them); while enabled each call records an event before the main
- * kernel, between the two kernels and after the combine kernel.  kv_profile_read
- * waits for the recorded calls, returns the summed durations in milliseconds and the
- * number of calls, and rearms the same events.  Not thread-safe against concurrent
- * kv_decode_attn calls on other threads beyond a mutex around the slot counter.
+ * Timing of the main attention kernel with HIP events on the call's own stream (the paper
+ * reports the attention kernel's duration, Table 2).  kv_profile_enable(n) creates events for
+ * the next n kv_decode_attn calls (host-side allocation, not on the timed path; n = 0 frees
+ * them); while enabled each call records one event before and one after its main kernel.
+ * kv_profile_read waits for the recorded calls, returns the summed kernel durations in
+ * milliseconds and the number of calls, and rearms the same events.  Calls from several
+ * threads share one slot counter under a mutex.
  */
 int kv_profile_enable(int max_calls);
-int kv_profile_read(double* main_ms_sum, double* combine_ms_sum, int* calls);
+int kv_profile_read(double* main_ms_sum, int* calls);
 
 /* Text of the last error on this thread; never NULL. */
 const char* kv_last_error(void);

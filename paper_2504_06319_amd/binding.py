@@ -81,8 +81,7 @@ def load_library():
             lib.kv_profile_enable.restype = ctypes.c_int
             lib.kv_profile_enable.argtypes = [ctypes.c_int]
             lib.kv_profile_read.restype = ctypes.c_int
-            lib.kv_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
-                                            ctypes.POINTER(ctypes.c_int)]
+            lib.kv_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
             lib.kv_last_error.restype = ctypes.c_char_p
             lib.kv_version.restype = ctypes.c_int
             lib.kv_block_bytes.restype = ctypes.c_size_t
@@ -217,10 +216,10 @@ def kv_profile_enable(max_calls: int):
 
 
 def kv_profile_read():
-    """(main kernel ms summed, combine kernel ms summed, calls) since the last read."""
-    a, b, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
-    _check(load_library().kv_profile_read(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)))
-    return a.value, b.value, n.value
+    """(main kernel ms summed, calls) since the last read."""
+    a, n = ctypes.c_double(), ctypes.c_int()
+    _check(load_library().kv_profile_read(ctypes.byref(a), ctypes.byref(n)))
+    return a.value, n.value
 
 
 def kv_block_bytes(elem_bytes: int, head_dim: int, block_size: int) -> int:

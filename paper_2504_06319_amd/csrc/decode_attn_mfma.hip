@@ -11,9 +11,10 @@
 // T and its own range from context_lens with a wave-wide scan; nothing returns to the
 // host.  A wave that covers a unit completely writes the output rows itself; a wave whose
 // range cuts a unit writes an unnormalised partial (at most two per wave: the piece at
-// the start and the piece at the end of its range), bumps the unit's arrival counter, and
-// the wave that arrives last merges all pieces of the unit and writes its rows.  No wave
-// ever waits for another one.
+// the start and the piece at the end of its range) that the finalize kernel merges.
+// (Merging inside this kernel, by the worker whose piece arrives last, was measured: the
+// device-scope publication and the dependent loads at the very end of every range cost as
+// much as the second launch, so the simpler two-kernel form stayed.)
 //
 // Prefetch (Algorithm 1 generalised to distance PD): a wave owns PD + 1 LDS stages.
 // Per iteration it waits for the current tile, issues the asynchronous global->LDS
@@ -35,6 +36,8 @@
 // avoided by permuting which 16-byte chunk of a row each lane fetches: K rows are stored
 // with chunk index XOR row, V rows with chunk index XOR 2*(row % 8).
 #include "kv_common.h"
+
+#include <type_traits>
 
 namespace kvp {
 
@@ -127,7 +130,6 @@ struct Cursor {
     int j;        // tile index inside the sequence
     int ntiles;   // tiles of sequence b
     int n;        // clamped context length of sequence b
-    int cum;      // tiles (per kv head) of the sequences before b
 };
 
 typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;   // uniform loads become scalar loads
@@ -184,84 +186,6 @@ __device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_wo
     return (int64_t)worker * T / num_workers;
 }
 
-__device__ __forceinline__ float wave_max_f32(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-    return v;
-}
-__device__ __forceinline__ float wave_sum_f32(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
-}
-
-// Merge of the np pieces of unit (b, kvh), run by the wave whose piece arrived last:
-//   out[g, :] = sum_i 2^(m_i - m*) acc_i / sum_i 2^(m_i - m*) l_i,   m* = max_i m_i.
-// Piece i was written by worker w0 + i; only the first worker can hold the unit as the piece at the END
-// of its range (slot 1), every later worker holds it as the piece at the start (slot 0).
-// Heads are taken two at a time: the lower 32 lanes own four columns each of head 2hp, the upper 32 of
-// head 2hp + 1, so one 128-bit load per lane fetches a piece's accumulators of both heads.
-template <Elem E>
-__device__ __forceinline__ void merge_unit(const AttnParams& p, int b, int kvh, int w0, int np, int64_t ua,
-                                           int64_t T, int nw, int lane) {
-    constexpr int D = kD, PS = kPartialStride, U = 8;
-    const int G = p.G;
-    const int slot_first = range_start(w0, T, nw) < ua ? 1 : 0;
-    auto row_of = [&](int i) { return (int64_t)((w0 + i) * 2 + (i == 0 ? slot_first : 0)) * G; };
-    const int gsel = lane / 32, c = 4 * (lane % 32);
-#pragma unroll 1
-    for (int hp = 0; 2 * hp < G; ++hp) {
-        const int g0 = 2 * hp, g1 = min(g0 + 1, G - 1);
-        float ms0 = kNegBig, ms1 = kNegBig;
-        for (int base = 0; base < np; base += kWaveSize) {
-            const int i = base + lane;
-            if (i < np) {
-                const float* r = p.partials + (row_of(i) + g0) * PS;
-                ms0 = fmaxf(ms0, r[D]);
-                ms1 = fmaxf(ms1, r[(g1 - g0) * PS + D]);
-            }
-        }
-        ms0 = wave_max_f32(ms0);
-        ms1 = wave_max_f32(ms1);
-        float4v acc = {0.f, 0.f, 0.f, 0.f};
-        float den0 = 0.f, den1 = 0.f;
-        for (int base = 0; base < np; base += kWaveSize) {
-            const int i = base + lane;
-            float wa = 0.f, wb = 0.f;                        // weights of piece i for the two heads, held by lane i
-            if (i < np) {
-                const float* r = p.partials + (row_of(i) + g0) * PS;
-                wa = fast_exp2(r[D] - ms0);
-                den0 += wa * r[D + 1];
-                wb = fast_exp2(r[(g1 - g0) * PS + D] - ms1);
-                den1 += wb * r[(g1 - g0) * PS + D + 1];
-            }
-            const int cnt = min(kWaveSize, np - base);
-            for (int k0 = 0; k0 < cnt; k0 += U) {            // U independent 128-bit loads in flight
-                float4v v[U];
-                float wk[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int k = min(k0 + u, cnt - 1);      // stay on a real piece; surplus slots get weight 0
-                    const float wka = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wa), k));
-                    const float wkb = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wb), k));
-                    wk[u] = k0 + u < cnt ? (gsel ? wkb : wka) : 0.f;
-                    v[u] = *reinterpret_cast<const float4v*>(p.partials + (row_of(base + k) + (gsel ? g1 : g0)) * PS + c);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) acc += wk[u] * v[u];
-            }
-        }
-        den0 = wave_sum_f32(den0);
-        den1 = wave_sum_f32(den1);
-        if (gsel == 0 || g0 + 1 < G) {
-            const float inv = 1.0f / (gsel ? den1 : den0);
-            uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)b * p.out_stride_b +
-                             (int64_t)(kvh * G + (gsel ? g1 : g0)) * p.out_stride_h + c;
-            *reinterpret_cast<u32x2*>(orow) = u32x2{pack2<E>(acc[0] * inv, acc[1] * inv), pack2<E>(acc[2] * inv, acc[3] * inv)};
-        }
-    }
-}
-
 template <Elem E, int BS, int PD>
 __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     constexpr int D = kD;
@@ -281,15 +205,8 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     // ---- this worker's range of the flat tile space
     const int total = scan_total(cl, p.B, max_len, lane);
     const int64_t T = (int64_t)total * Hkv;
-    // empty sequences get zero rows: worker w takes sequences w, w + workers, ...
-    for (int b = worker; b < p.B; b += p.num_workers) {
-        if (clamp_len(cl[b], max_len) > 0) continue;
-        uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)b * p.out_stride_b;
-        for (int i = lane; i < p.Hq * (D / 8); i += kWaveSize)
-            *reinterpret_cast<u32x4*>(orow + (int64_t)(i / (D / 8)) * p.out_stride_h + (i % (D / 8)) * 8) = u32x4{0, 0, 0, 0};
-    }
-    // with fewer tiles than workers only the first T workers get a (one-tile) range, so that every
-    // active worker's range is non-empty
+    // with fewer tiles than workers only the first T workers get a (one-tile) range, so that every active
+    // worker's range is non-empty
     const int nw = T < p.num_workers ? (int)T : p.num_workers;
     if (worker >= nw) return;
     const int64_t r0 = range_start(worker, T, nw);
@@ -299,7 +216,6 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         int b0, cum0;
         scan_locate(cl, p.B, max_len, lane, Hkv, r0, b0, cum0);
         ca.b = b0;
-        ca.cum = cum0;
         ca.n = clamp_len(cl[b0], max_len);
         ca.ntiles = tiles_of(ca.n);
         const int rem = (int)(r0 - (int64_t)Hkv * cum0);
@@ -312,7 +228,6 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         if (++c.kvh < Hkv) return;
         c.kvh = 0;
         do {
-            c.cum += c.ntiles;
             ++c.b;
             c.n = clamp_len(cl[c.b], max_len);
             c.ntiles = tiles_of(c.n);
@@ -479,27 +394,12 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
                         const u32x2 w = {pack2<E>(o[cb][0] * inv, o[cb][1] * inv), pack2<E>(o[cb][2] * inv, o[cb][3] * inv)};
                         *reinterpret_cast<u32x2*>(orow + 16 * cb) = w;
                     }
-                } else {                                        // a cut unit: unnormalised partial piece
+                } else {                                        // a cut unit: unnormalised partial for the finalize kernel
                     const int slot = piece_at_range_start ? 0 : 1;
                     float* dst = p.partials + ((int64_t)(worker * 2 + slot) * G + lr) * kPartialStride;
 #pragma unroll
                     for (int cb = 0; cb < 8; ++cb) *reinterpret_cast<float4v*>(dst + 16 * cb + 4 * lq) = o[cb];
                     if (lq == 0) { dst[D] = m; dst[D + 1] = lt; }
-                }
-            }
-            if (!(piece_first_j == 0 && unit_end)) {
-                // which workers share this unit: the last worker whose range starts at or before the unit's
-                // first flat tile up to the last worker whose range starts before its end
-                const int64_t ua = (int64_t)Hkv * ca.cum + (int64_t)ca.kvh * ca.ntiles, ue = ua + ca.ntiles;
-                const int w0 = (int)(((ua + 1) * nw - 1) / T), w1 = (int)((ue * nw - 1) / T);
-                __threadfence();                                // release the piece before announcing it
-                int arrived = 0;
-                if (lane == 0) arrived = atomicAdd(p.unit_counters + ca.b * Hkv + ca.kvh, 1);
-                arrived = __builtin_amdgcn_readfirstlane(arrived);
-                if (arrived == w1 - w0) {                       // every other piece is already there: merge
-                    __threadfence();
-                    merge_unit<E>(p, ca.b, ca.kvh, w0, w1 - w0 + 1, ua, T, nw, lane);
-                    if (lane == 0) p.unit_counters[ca.b * Hkv + ca.kvh] = 0;    // ready for the next call
                 }
             }
 #pragma unroll
@@ -516,6 +416,79 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             }
         }
     }
+}
+
+// Merge of the pieces of every unit that more than one worker touched, and zero rows for empty
+// sequences.  One workgroup per (query head, sequence), one thread per output column.
+//   out[h, c] = sum_i 2^(m_i - m*) acc_i[c] / sum_i 2^(m_i - m*) l_i,   m* = max_i m_i
+// Piece i was written by worker w0 + i; only the first worker can hold the unit as the piece at the END
+// of its range (slot 1), every later worker holds it as the piece at the start (slot 0).
+// The kernel is a chain of dependent memory round trips, so it is written to have two of them: one pass
+// over context_lens, then every load of a batch of pieces (max, sum and accumulator column) in flight at
+// once, each thread keeping its own running (m*, sum, acc) across batches.
+template <Elem E>
+__global__ __launch_bounds__(kD) void attn_finalize_kernel(AttnParams p, int bs) {
+    constexpr int D = kD, PS = kPartialStride;
+    const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x, lane = c % kWaveSize;
+    const int G = p.G, Hkv = p.Hkv, kvh = h / G, g = h % G;
+    const int max_len = p.MB * bs;
+    const_i32_ptr cl = (const_i32_ptr)p.context_lens;
+    uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)b * p.out_stride_b + (int64_t)h * p.out_stride_h;
+
+    // one pass over the lengths: tiles of the batch, of the sequences before b, and of b itself
+    int total = 0, cum = 0, nt = 0;
+    for (int base = 0; base < p.B; base += kWaveSize) {
+        const int idx = base + lane;
+        const int t = idx < p.B ? tiles_of(clamp_len(cl[idx], max_len)) : 0;
+        total += wave_sum_i32(t);
+        cum += wave_sum_i32(idx < b ? t : 0);
+        if (b >= base && b < base + kWaveSize) nt = __builtin_amdgcn_readlane(t, b - base);
+    }
+    if (nt == 0) {                                  // empty context: zero row
+        orow[c] = 0;
+        return;
+    }
+    const int64_t T = (int64_t)total * Hkv;
+    const int nw = T < p.num_workers ? (int)T : p.num_workers;
+    const int64_t a = (int64_t)Hkv * cum + (int64_t)kvh * nt, end = a + nt;     // the unit's flat tile range
+    const int w0 = (int)(((a + 1) * nw - 1) / T);   // last worker whose range starts at or before a
+    const int w1 = (int)((end * nw - 1) / T);       // last worker whose range starts before end
+    if (w0 == w1) return;                           // one worker covered the unit and wrote the rows itself
+    const int np = w1 - w0 + 1;
+    const int slot_first = range_start(w0, T, nw) < a ? 1 : 0;
+    const float* first_row = p.partials + ((int64_t)(w0 * 2 + slot_first) * G + g) * PS;
+    const float* later_rows = p.partials + ((int64_t)(w0 * 2) * G + g) * PS;     // + i * 2 * G * PS for piece i >= 1
+
+    float num = 0.f, den = 0.f, mrun = kNegBig;
+    auto batch = [&](int base, int cnt, auto tag) {
+        constexpr int U = decltype(tag)::value;
+        float2 ml[U];
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = base + min(u, cnt - 1);   // stay on a real piece; surplus slots are ignored below
+            const float* row = i == 0 ? first_row : later_rows + (int64_t)i * 2 * G * PS;
+            ml[u] = *reinterpret_cast<const float2*>(row + D);
+            v[u] = row[c];
+        }
+        float mb = mrun;
+#pragma unroll
+        for (int u = 0; u < U; ++u) if (u < cnt) mb = fmaxf(mb, ml[u].x);
+        const float resc = fast_exp2(mrun - mb);
+        num *= resc;
+        den *= resc;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float w = u < cnt ? fast_exp2(ml[u].x - mb) : 0.f;
+            num += w * v[u];
+            den += w * ml[u].y;
+        }
+        mrun = mb;
+    };
+    int base = 0;
+    for (; np - base > 8; base += 32) batch(base, min(32, np - base), std::integral_constant<int, 32>{});
+    if (base < np) batch(base, np - base, std::integral_constant<int, 8>{});
+    orow[c] = pack1<E>(num / den);
 }
 
 template <Elem E, int BS, int PD>
@@ -544,6 +517,14 @@ int mfma_worker_lds_bytes(int prefetch_distance) { return (prefetch_distance + 1
 // Bytes of partial storage for a launch with this many workers.
 size_t mfma_partial_bytes(int num_workers, int G) {
     return (size_t)num_workers * 2 * G * kPartialStride * sizeof(float);
+}
+
+// Merge kernel of the head_dim-128 path; always launched after the main kernel (it also writes the zero
+// rows of empty sequences).
+int launch_finalize_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream) {
+    if (elem == (int)Elem::F16) hipLaunchKernelGGL(attn_finalize_kernel<Elem::F16>, dim3(p.Hq, p.B), dim3(kD), 0, stream, p, bs);
+    else hipLaunchKernelGGL(attn_finalize_kernel<Elem::BF16>, dim3(p.Hq, p.B), dim3(kD), 0, stream, p, bs);
+    return 0;
 }
 
 // head_dim 128 only.  Returns 0 or -1 (no such instantiation).

@@ -63,11 +63,11 @@ int part_tokens() {
 }
 
 size_t workspace_bytes(int B, int Hq, int d, int64_t max_context, int P) {
-    if (d == 128)   // persistent-worker kernel: arrival counters, then two partial pieces per worker of the largest launch
-        return kvp::kCounterRegionBytes + kvp::mfma_partial_bytes(kvp::kMaxMfmaWorkers, Hq < 16 ? Hq : 16);
+    if (d == 128)   // persistent-worker kernel: two partial pieces per worker, sized for the largest launch
+        return kvp::mfma_partial_bytes(kvp::kMaxMfmaWorkers, Hq < 16 ? Hq : 16);
     if (max_context <= P) return 0;
     int64_t np = (max_context + P - 1) / P;
-    return kvp::kCounterRegionBytes + (size_t)B * Hq * np * (d + 2) * sizeof(float);
+    return (size_t)B * Hq * np * (d + 2) * sizeof(float);
 }
 
 bool dense_tile(const kv_tensor* t) {   // [NBLK, Hkv, bs, d] with the [bs, d] tile contiguous
@@ -156,7 +156,6 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.prefetch_distance = prefetch_distance;
     p.scale_log2e = scale * kvp::kLog2e;
     p.partials = nullptr;
-    p.unit_counters = nullptr;
     r->elem = q->dtype; r->d = (int)d; r->bs = block_size;
     r->split = p.NP > 1;
     p.num_workers = 0;
@@ -166,11 +165,8 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
         if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
         int nw = cus * waves_per_cu(prefetch_distance);
         p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
-        if (B * num_kv_heads > kvp::kMaxMfmaUnits)
-            return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: %lld (sequence, kv head) units exceed %d",
-                        (long long)(B * num_kv_heads), kvp::kMaxMfmaUnits);
-        need = kvp::kCounterRegionBytes + kvp::mfma_partial_bytes(p.num_workers, G);
-        r->split = false;              // pieces are merged inside the main kernel
+        need = kvp::mfma_partial_bytes(p.num_workers, G);
+        r->split = false;              // the finalize kernel is launched with the main kernel
     } else if (r->split) {
         need = workspace_bytes((int)B, (int)Hq, (int)d, max_context, P);
     }
@@ -178,21 +174,18 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
         std::lock_guard<std::mutex> lock(g_ws_mutex);
         if (!g_ws_ptr || g_ws_bytes < need)
             return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
-        // the head of the workspace belongs to the arrival counters whichever kernel runs
-        p.unit_counters = (int32_t*)g_ws_ptr;
-        p.partials = (float*)((char*)g_ws_ptr + kvp::kCounterRegionBytes);
+        p.partials = (float*)g_ws_ptr;
     }
     return KV_OK;
 }
 
-// Optional per-call timing: three events per call (before the main kernel, between the
-// kernels, after the combine kernel), recorded on the call's stream.
+// Optional per-call timing: two events per call, one on each side of the main attention kernel, recorded on
+// the call's stream (the merge kernel that follows is outside the bracket).
 std::mutex g_prof_mutex;
 std::vector<hipEvent_t> g_prof_events;
 int g_prof_capacity = 0, g_prof_calls = 0;
-std::vector<char> g_prof_split;
 
-hipEvent_t prof_event(int call, int which) { return g_prof_events[(size_t)call * 3 + which]; }
+hipEvent_t prof_event(int call, int which) { return g_prof_events[(size_t)call * 2 + which]; }
 
 int check_launch(const char* what) {
     hipError_t e = hipGetLastError();
@@ -205,7 +198,6 @@ int run_attn(const Resolved& r, hipStream_t stream) {
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: group size %d with head_dim %d not covered", r.p.G, r.d);
     std::unique_lock<std::mutex> prof_lock(g_prof_mutex);
     const int slot = (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity) ? g_prof_calls++ : -1;
-    if (slot >= 0) g_prof_split[slot] = r.split;
     prof_lock.unlock();
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), stream);
     // head_dim 128 runs on the matrix cores with the LDS prefetch ring; head_dim 64 on the vector-ALU kernel
@@ -216,11 +208,13 @@ int run_attn(const Resolved& r, hipStream_t stream) {
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);
-    if (r.split) {
+    if (r.d == 128) {
+        kvp::launch_finalize_mfma(r.p, r.elem, r.bs, stream);
+        if (int rc = check_launch("kv_decode_attn finalize kernel")) return rc;
+    } else if (r.split) {
         kvp::launch_reduce(r.p, r.elem, r.d, r.bs, stream);
         if (int rc = check_launch("kv_decode_attn combine kernel")) return rc;
     }
-    if (slot >= 0) (void)hipEventRecord(prof_event(slot, 2), stream);
     return KV_OK;
 }
 
@@ -260,14 +254,6 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {
     if ((dev_ptr == nullptr) != (bytes == 0))
         return fail(KV_ERR_INVALID, "kv_decode_set_workspace: pointer and size must both be set or both be zero");
     if (((uintptr_t)dev_ptr) % 16) return fail(KV_ERR_INVALID, "kv_decode_set_workspace: pointer must be 16-byte aligned");
-    if (dev_ptr) {
-        // the head of the workspace holds the arrival counters of the head_dim-128 kernel; they must read zero
-        // before the first call and every call leaves them at zero
-        const size_t head = bytes < kvp::kCounterRegionBytes ? bytes : kvp::kCounterRegionBytes;
-        hipError_t e = hipMemset(dev_ptr, 0, head);
-        if (e == hipSuccess) e = hipDeviceSynchronize();
-        if (e != hipSuccess) return fail(KV_ERR_HIP, "kv_decode_set_workspace: %s", hipGetErrorString(e));
-    }
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     g_ws_ptr = dev_ptr;
     g_ws_bytes = bytes;
@@ -300,10 +286,9 @@ int kv_profile_enable(int max_calls) {
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     for (hipEvent_t ev : g_prof_events) (void)hipEventDestroy(ev);
     g_prof_events.clear();
-    g_prof_split.assign((size_t)max_calls, 0);
     g_prof_capacity = 0;
     g_prof_calls = 0;
-    for (int i = 0; i < 3 * max_calls; ++i) {
+    for (int i = 0; i < 2 * max_calls; ++i) {
         hipEvent_t ev;
         hipError_t e = hipEventCreate(&ev);
         if (e != hipSuccess) {
@@ -317,18 +302,17 @@ int kv_profile_enable(int max_calls) {
     return KV_OK;
 }
 
-int kv_profile_read(double* main_ms_sum, double* combine_ms_sum, int* calls) {
-    if (!main_ms_sum || !combine_ms_sum || !calls) return fail(KV_ERR_INVALID, "kv_profile_read: null output");
+int kv_profile_read(double* main_ms_sum, int* calls) {
+    if (!main_ms_sum || !calls) return fail(KV_ERR_INVALID, "kv_profile_read: null output");
     std::lock_guard<std::mutex> lock(g_prof_mutex);
-    *main_ms_sum = 0; *combine_ms_sum = 0; *calls = g_prof_calls;
+    *main_ms_sum = 0;
+    *calls = g_prof_calls;
     for (int i = 0; i < g_prof_calls; ++i) {
-        hipError_t e = hipEventSynchronize(prof_event(i, 2));
-        float a = 0.f, b = 0.f;
+        hipError_t e = hipEventSynchronize(prof_event(i, 1));
+        float a = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&a, prof_event(i, 0), prof_event(i, 1));
-        if (e == hipSuccess) e = hipEventElapsedTime(&b, prof_event(i, 1), prof_event(i, 2));
         if (e != hipSuccess) return fail(KV_ERR_HIP, "kv_profile_read: %s", hipGetErrorString(e));
         *main_ms_sum += a;
-        *combine_ms_sum += b;
     }
     g_prof_calls = 0;
     return KV_OK;

@@ -20,7 +20,6 @@ struct AttnParams {
     const int32_t* context_lens;
     void* out;
     float* partials;          // split-KV scratch: unnormalised acc, running max (log2 domain), sum per piece
-    int32_t* unit_counters;   // [B * Hkv] arrival counters of the head_dim-128 kernel, zero between calls
     int64_t q_stride_b, q_stride_h;
     int64_t kv_stride_blk, kv_stride_h;
     int64_t v_stride_blk, v_stride_h;
@@ -95,11 +94,10 @@ __device__ __forceinline__ float group_sum(float x) {
 
 int launch_attn_valu(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_attn_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream);
+int launch_finalize_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream);
 int mfma_worker_lds_bytes(int prefetch_distance);
 size_t mfma_partial_bytes(int num_workers, int G);
 constexpr int kMaxMfmaWorkers = 4096;
-constexpr int kMaxMfmaUnits = 262144;                             // (sequence, kv head) pairs with a counter
-constexpr size_t kCounterRegionBytes = (size_t)kMaxMfmaUnits * 4; // head of the workspace, zeroed at registration
 int launch_reduce(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 
 }  // namespace kvp

@@ -47,11 +47,10 @@ def test_workspace_size_formula():
     # head_dim 64: one partial per (sequence, head, partition); nothing when one partition suffices
     assert kv.kv_decode_workspace_bytes(8, 32, 64, P, 16) == 0
     np_ = -(-32768 // P)
-    assert kv.kv_decode_workspace_bytes(8, 32, 64, 32768, 16) == (1 << 20) + 8 * 32 * np_ * 66 * 4
+    assert kv.kv_decode_workspace_bytes(8, 32, 64, 32768, 16) == 8 * 32 * np_ * 66 * 4
     # head_dim 128: two partial pieces of min(Hq, 16) rows of 132 floats for each of at most 4096 workers
-    # plus 1 MiB of arrival counters
-    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == (1 << 20) + 4096 * 2 * 16 * 132 * 4
-    assert kv.kv_decode_workspace_bytes(1, 4, 128, 16, 16) == (1 << 20) + 4096 * 2 * 4 * 132 * 4
+    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == 4096 * 2 * 16 * 132 * 4
+    assert kv.kv_decode_workspace_bytes(1, 4, 128, 16, 16) == 4096 * 2 * 4 * 132 * 4
     with pytest.raises(kv.KVError):
         kv.kv_decode_set_partition_tokens(100)
     kv.kv_decode_set_partition_tokens(1024)
