@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--waves-per-cu", type=int, default=0, help="persistent waves per compute unit (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the prefetch-off leg and the other workloads")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run plain 1 GiB device copies, so a counter run sees a copy kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only; run with --gpus 1 "
@@ -117,6 +119,15 @@ def main():
         kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"])
         ms, main_ms = timed_steps(kv, torch, cases, pd, steps, warmup)
         return cfg, cases, kvb, ms, main_ms
+
+    if args.traffic_calibration:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     pd_on = args.prefetch_distance if args.prefetch_distance is not None else 2
     log(f"[bench] workload {args.workload} prefetch_distance {pd_on}")
