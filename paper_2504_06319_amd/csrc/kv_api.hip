@@ -187,6 +187,12 @@ int g_prof_capacity = 0, g_prof_calls = 0;
 
 hipEvent_t prof_event(int call, int which) { return g_prof_events[(size_t)call * 2 + which]; }
 
+// Side stream of the layer stack's cross-layer touch (default priority, created on first use).
+std::mutex g_side_mutex;
+hipStream_t g_side_stream = nullptr;
+hipEvent_t g_fork_event = nullptr, g_join_event = nullptr;
+constexpr int kTouchTiles = 4;          // leading 16-token tiles of every worker's range that get touched
+
 int check_launch(const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
@@ -238,10 +244,72 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
                          const kv_tensor* block_tables, const kv_tensor* context_lens,
                          kv_tensor* const* outs, float scale, int num_kv_heads, int block_size,
                          int prefetch_distance, int cross_layer_prefetch, void* stream) {
-    (void)num_layers; (void)x; (void)weights; (void)gemm_out; (void)q; (void)k_caches; (void)v_caches;
-    (void)block_tables; (void)context_lens; (void)outs; (void)scale; (void)num_kv_heads; (void)block_size;
-    (void)prefetch_distance; (void)cross_layer_prefetch; (void)stream;
-    return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: not built yet");
+    if (num_layers < 1 || num_layers > 4096) return fail(KV_ERR_INVALID, "kv_decode_layerstack: %d layers", num_layers);
+    if (!x || !weights || !gemm_out || !k_caches || !v_caches || !outs || !block_tables || !context_lens)
+        return fail(KV_ERR_INVALID, "kv_decode_layerstack: null argument");
+    if (!x->data || !gemm_out->data) return fail(KV_ERR_INVALID, "kv_decode_layerstack: null data pointer");
+    if (x->ndim != 2 || gemm_out->ndim != 2) return fail(KV_ERR_INVALID, "kv_decode_layerstack: x and gemm_out must have rank 2");
+    if (x->dtype != KV_BF16 || gemm_out->dtype != KV_BF16)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: x and gemm_out must be bf16");
+    if (x->stride[1] != 1 || gemm_out->stride[1] != 1) return fail(KV_ERR_INVALID, "kv_decode_layerstack: innermost stride must be 1");
+    const int64_t M = x->shape[0], K = x->shape[1], N = gemm_out->shape[1];
+    if (gemm_out->shape[0] != M) return fail(KV_ERR_INVALID, "kv_decode_layerstack: gemm_out rows differ from x");
+    if (((uintptr_t)x->data) % 16 || ((uintptr_t)gemm_out->data) % 16 || x->stride[0] % 8 || gemm_out->stride[0] % 8)
+        return fail(KV_ERR_INVALID, "kv_decode_layerstack: x and gemm_out rows must be 16-byte aligned");
+    for (int l = 0; l < num_layers; ++l) {
+        const kv_tensor* w = weights[l];
+        if (!w || !w->data || !k_caches[l] || !v_caches[l] || !outs[l] || (q && !q[l]))
+            return fail(KV_ERR_INVALID, "kv_decode_layerstack: null tensor in layer %d", l);
+        if (w->ndim != 2 || w->dtype != KV_BF16 || w->shape[0] != K || w->shape[1] != N || w->stride[1] != 1 ||
+            ((uintptr_t)w->data) % 16 || w->stride[0] % 8)
+            return fail(KV_ERR_INVALID, "kv_decode_layerstack: weights[%d] must be dense bf16 [%lld, %lld]", l, (long long)K, (long long)N);
+        if (outs[l]->ndim != 3) return fail(KV_ERR_INVALID, "kv_decode_layerstack: outs[%d] must have rank 3", l);
+    }
+    const int64_t B = outs[0]->shape[0], Hq = outs[0]->shape[1], d = outs[0]->shape[2];
+    if (B != M) return fail(KV_ERR_INVALID, "kv_decode_layerstack: outs batch %lld differs from x rows %lld", (long long)B, (long long)M);
+    if (!q && N < Hq * d) return fail(KV_ERR_INVALID, "kv_decode_layerstack: gemm_out has %lld columns, queries need %lld", (long long)N, (long long)(Hq * d));
+    if (M > 128 || K % 128 || K < 128 || N % 64 || N < 64)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: GEMM shape [%lld x %lld] . [%lld x %lld] not covered (rows <= 128, K %% 128 == 0, N %% 64 == 0)",
+                    (long long)M, (long long)K, (long long)K, (long long)N);
+    hipStream_t main_stream = (hipStream_t)stream;
+
+    // queries of layer l: the caller's tensor, or the leading Hq*d columns of the GEMM output viewed [B, Hq, d]
+    kv_tensor qview;
+    qview.data = gemm_out->data; qview.dtype = KV_BF16; qview.ndim = 3;
+    qview.shape[0] = B; qview.shape[1] = Hq; qview.shape[2] = d;
+    qview.stride[0] = gemm_out->stride[0]; qview.stride[1] = d; qview.stride[2] = 1;
+
+    const bool touch = cross_layer_prefetch != 0 && d == 128;
+    if (touch) {
+        std::lock_guard<std::mutex> lock(g_side_mutex);
+        if (!g_side_stream) {
+            hipError_t e = hipStreamCreateWithFlags(&g_side_stream, hipStreamNonBlocking);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&g_fork_event, hipEventDisableTiming);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&g_join_event, hipEventDisableTiming);
+            if (e != hipSuccess) return fail(KV_ERR_HIP, "kv_decode_layerstack: side stream: %s", hipGetErrorString(e));
+        }
+    }
+    for (int l = 0; l < num_layers; ++l) {
+        const kv_tensor* ql = q ? q[l] : &qview;
+        Resolved r;
+        if (int rc = resolve(ql, k_caches[l], v_caches[l], block_tables, context_lens, outs[l], scale, num_kv_heads,
+                             block_size, prefetch_distance, &r))
+            return rc;
+        if (touch) {        // fork: touch this layer's leading KV tiles while the dense layer runs
+            (void)hipEventRecord(g_fork_event, main_stream);
+            (void)hipStreamWaitEvent(g_side_stream, g_fork_event, 0);
+            kvp::launch_touch_mfma(r.p, r.bs, kTouchTiles, (uint32_t*)r.p.partials, g_side_stream);
+            (void)hipEventRecord(g_join_event, g_side_stream);
+        }
+        const int grc = kvp::launch_layer_gemm(x->data, weights[l]->data, gemm_out->data, (int)M, (int)K, (int)N,
+                                               x->stride[0], weights[l]->stride[0], gemm_out->stride[0], main_stream);
+        if (grc == -2) return fail(KV_ERR_HIP, "kv_decode_layerstack: could not raise the dynamic LDS limit of the GEMM kernel");
+        if (grc != 0) return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: GEMM shape not covered");
+        if (int rc = check_launch("kv_decode_layerstack GEMM kernel")) return rc;
+        if (touch) (void)hipStreamWaitEvent(main_stream, g_join_event, 0);
+        if (int rc = run_attn(r, main_stream)) return rc;
+    }
+    return KV_OK;
 }
 
 size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size) {

@@ -81,8 +81,11 @@ def randn16(shape, dtype: str, seed: int, device) -> torch.Tensor:
 
 
 def make_case(cfg: dict, seed: int, device="cpu", poison: bool = False, table_width: int | None = None,
-              lens=None) -> dict:
+              lens=None, data_seed: int | None = None) -> dict:
     """All tensors of one attention call.
+
+    Lengths and paging come from ``seed``; the N(0,1) values from ``data_seed`` (default ``seed``), so
+    the layers of a stack can share one block table and hold different data.
 
     poison=True writes NaN into every cache slot no sequence owns (the unowned pool
     blocks, the poison block, and the tail of each sequence's last block); a correct
@@ -92,9 +95,10 @@ def make_case(cfg: dict, seed: int, device="cpu", poison: bool = False, table_wi
     B, Hq, Hkv, d, bs = len(lens), cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["bs"]
     tables, nblk, poison_id = block_tables(lens, bs, seed, width=table_width)
     dt = cfg["dtype"]
-    q = randn16((B, Hq, d), dt, seed + 1, device)
-    k_cache = randn16((nblk, Hkv, bs, d), dt, seed + 2, device)
-    v_cache = randn16((nblk, Hkv, bs, d), dt, seed + 3, device)
+    ds = seed if data_seed is None else data_seed
+    q = randn16((B, Hq, d), dt, ds + 1, device)
+    k_cache = randn16((nblk, Hkv, bs, d), dt, ds + 2, device)
+    v_cache = randn16((nblk, Hkv, bs, d), dt, ds + 3, device)
     if poison:
         owned = torch.zeros(nblk, dtype=torch.bool)
         tail_mask = torch.zeros((nblk, bs), dtype=torch.bool)

@@ -1,0 +1,123 @@
+"""Parity of kv_decode_layerstack (dense layer + paged decode attention per layer) with the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2504_06319_amd as kv
+from paper_2504_06319_amd import synth
+from kvcheck import compare
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _stack(L, B, Hq, Hkv, d, bs, K, N, lens, seed, poison=True):
+    cfg = dict(Hq=Hq, Hkv=Hkv, d=d, bs=bs, dtype="bf16")
+    # one paging for the whole stack, different K/V values per layer
+    layers = [synth.make_case(cfg, seed, DEV, poison=poison, lens=lens, data_seed=seed + 1000 * l) for l in range(L)]
+    x = synth.randn16((B, K), "bf16", seed + 11, DEV)
+    ws = [synth.randn16((K, N), "bf16", seed + 13 + l, DEV) * 0.02 for l in range(L)]
+    ws = [w.contiguous() for w in ws]
+    y = torch.full((B, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    outs = [torch.full((B, Hq, d), float("nan"), dtype=torch.bfloat16, device=DEV) for _ in range(L)]
+    return cfg, layers, x, ws, y, outs
+
+
+def _run(layers, x, ws, y, outs, q=None, pd=2, cross=0):
+    c0 = layers[0]
+    kv.kv_decode_layerstack(x, ws, y, q, [c["k_cache"] for c in layers], [c["v_cache"] for c in layers],
+                            c0["block_tables"], c0["context_lens"], outs, c0["scale"], c0["num_kv_heads"],
+                            c0["block_size"], pd, cross)
+    torch.cuda.synchronize()
+
+
+def _ulp_close_bf16(got_bits, want_bits):
+    """The GPU sums bf16 products in fp32 (MFMA), the oracle in fp64; both round to bf16.  The results agree to
+    one bf16 unit in the last place (2^-7 relative) plus the fp32 accumulation error of a K-term sum of
+    magnitude ~1 (K * 2^-24 <= 2.5e-4 at K = 4096), which matters only for sums that cancel to near zero."""
+    g = (got_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    w = (want_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return bool((np.abs(g - w) <= 2.0 ** -7 * np.abs(w) + 2.5e-4).all())
+
+
+@pytest.mark.parametrize("B", [128, 5])
+@pytest.mark.parametrize("cross", [0, 1])
+def test_small_stack_matches_oracle(B, cross):
+    L, Hq, Hkv, d, bs, K, N = 3, 8, 2, 128, 16, 256, 1280
+    lens = np.random.default_rng(B).integers(1, 700, B).tolist()
+    cfg, layers, x, ws, y, outs = _stack(L, B, Hq, Hkv, d, bs, K, N, lens, 61)
+    _run(layers, x, ws, y, outs, cross=cross)
+    xb = oracle.bits_of(x)
+    for l in range(L):
+        c = layers[l]
+        # the GEMM output left in y is the last layer's; recompute each layer's on the oracle
+        ybits, want = oracle.layerstack_layer(xb, oracle.bits_of(ws[l]), oracle.bits_of(c["k_cache"]),
+                                              oracle.bits_of(c["v_cache"]), c["block_tables"].cpu().numpy(),
+                                              c["context_lens"].cpu().numpy(), c["scale"], Hq, d)
+        compare(outs[l], want, f"layer {l}")
+        if l == L - 1:
+            assert _ulp_close_bf16(oracle.bits_of(y), ybits)
+            # attention on the queries exactly as the GPU stored them
+            qg = oracle.bits_of(y)[:, : Hq * d].reshape(B, Hq, d)
+            want_q = oracle.paged_attention(qg, oracle.bits_of(c["k_cache"]), oracle.bits_of(c["v_cache"]),
+                                            c["block_tables"].cpu().numpy(), c["context_lens"].cpu().numpy(),
+                                            c["scale"], "bf16")
+            compare(outs[l], want_q, f"layer {l} on the GPU's own queries")
+
+
+def test_explicit_queries_bypass_the_gemm_output():
+    L, B, Hq, Hkv, d, bs, K, N = 2, 16, 8, 2, 128, 16, 128, 64
+    lens = [100 + 37 * i for i in range(B)]
+    cfg, layers, x, ws, y, outs = _stack(L, B, Hq, Hkv, d, bs, K, N, lens, 67)
+    _run(layers, x, ws, y, outs, q=[c["q"] for c in layers])
+    for l, c in enumerate(layers):
+        want = oracle.paged_attention(oracle.bits_of(c["q"]), oracle.bits_of(c["k_cache"]), oracle.bits_of(c["v_cache"]),
+                                      c["block_tables"].cpu().numpy(), c["context_lens"].cpu().numpy(), c["scale"], "bf16")
+        compare(outs[l], want, f"layer {l}")
+    assert _ulp_close_bf16(oracle.bits_of(y), oracle.layer_gemm_bf16(oracle.bits_of(x), oracle.bits_of(ws[-1])))
+
+
+def test_gemm_alone_on_the_benchmark_shape():
+    """The stand-in dense layer at its full shape [128 x 4096] . [4096 x 14336], sampled columns on the oracle."""
+    B, K, N, Hq, Hkv, d, bs = 128, 4096, 14336, 32, 8, 128, 16
+    cfg, layers, x, ws, y, outs = _stack(1, B, Hq, Hkv, d, bs, K, N, [64] * B, 71, poison=False)
+    _run(layers, x, ws, y, outs)
+    cols = np.random.default_rng(0).choice(N, 96, replace=False)
+    cols = np.concatenate([cols, [0, 63, 64, N - 1]])
+    wsub = oracle.bits_of(ws[0])[:, cols]
+    want = oracle.layer_gemm_bf16(oracle.bits_of(x), np.ascontiguousarray(wsub))
+    got = oracle.bits_of(y)[:, cols]
+    assert _ulp_close_bf16(got, want)
+
+
+def test_unsupported_gemm_shapes_are_rejected():
+    cfg, layers, x, ws, y, outs = _stack(1, 4, 8, 2, 128, 16, 128, 1024, [10] * 4, 73, poison=False)
+    with pytest.raises(kv.KVError) as e:
+        _run(layers, x[:, :96].contiguous(), [ws[0][:96].contiguous()], y, outs)      # K = 96 is not a multiple of 128
+    assert e.value.status == 2
+    with pytest.raises(kv.KVError) as e:
+        _run(layers, x, ws, y[:, :512].contiguous(), outs)          # too few columns for the queries
+    assert e.value.status == 1
+
+
+def test_layer_stack_configuration_sampled():
+    """Benchmark configuration 4 at full width (batch 128, 4096 x 14336 dense layer, contexts in [2048, 4096])
+    with 3 of its 32 layers resident; sampled (sequence, head) rows of every layer on the oracle."""
+    cfg = synth.CONFIGS[4]
+    L = 3
+    lens = synth.context_lengths(cfg, synth.config_seed(4))
+    _, layers, x, ws, y, outs = _stack(L, cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["bs"], cfg["gemm_k"],
+                                       cfg["gemm_n"], lens, synth.config_seed(4), poison=False)
+    _run(layers, x, ws, y, outs, cross=1)
+    rng = np.random.default_rng(4)
+    pairs = np.array([(b, h) for b in rng.choice(cfg["B"], 6, replace=False) for h in rng.choice(cfg["Hq"], 4, replace=False)], np.int32)
+    xb = oracle.bits_of(x)
+    for l, c in enumerate(layers):
+        _, want = oracle.layerstack_layer(xb, oracle.bits_of(ws[l]), oracle.bits_of(c["k_cache"]), oracle.bits_of(c["v_cache"]),
+                                          c["block_tables"].cpu().numpy(), c["context_lens"].cpu().numpy(), c["scale"],
+                                          cfg["Hq"], cfg["d"], pairs)
+        sub = outs[l][torch.from_numpy(pairs[:, 0]).long().to(DEV), torch.from_numpy(pairs[:, 1]).long().to(DEV)]
+        compare(sub, want, f"stack layer {l}")
