@@ -45,6 +45,38 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
     return (t1 - t0) * 1e3 / steps, main_ms / n
 
 
+def layer_stack(kv, torch, synth, dev, steps, warmup, pd, cross, layers=None):
+    """Benchmark configuration 4: `layers` x (dense layer [128 x 4096].[4096 x 14336] + paged decode attention on
+    that layer's own KV cache).  Returns ms per stack pass and the bytes one pass must move."""
+    cfg = synth.CONFIGS[4]
+    L = layers or cfg["layers"]
+    seed = synth.config_seed(4)
+    lens = synth.context_lengths(cfg, seed)
+    cases = [synth.make_case(cfg, seed, dev, lens=lens, data_seed=seed + 1000 * l) for l in range(L)]
+    x = synth.randn16((cfg["B"], cfg["gemm_k"]), "bf16", seed + 11, dev)
+    # weights ~ N(0, 0.02), handed over in the library's tile-packed layout (set-up time, not timed)
+    ws = [kv.pack_weights(synth.randn16((cfg["gemm_k"], cfg["gemm_n"]), "bf16", seed + 13 + l, dev) * 0.02) for l in range(L)]
+    y = torch.empty((cfg["B"], cfg["gemm_n"]), dtype=torch.bfloat16, device=dev)
+    outs = [torch.empty_like(c["q"]) for c in cases]
+    c0 = cases[0]
+    ks, vs = [c["k_cache"] for c in cases], [c["v_cache"] for c in cases]
+
+    def step():
+        kv.kv_decode_layerstack(x, ws, y, None, ks, vs, c0["block_tables"], c0["context_lens"], outs, c0["scale"],
+                                c0["num_kv_heads"], c0["block_size"], pd, cross)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    kvb = synth.kv_bytes(lens, cfg["Hkv"], cfg["d"]) * L
+    wb = cfg["gemm_k"] * cfg["gemm_n"] * 2 * L
+    return ms, kvb, wb, cfg, L
+
+
 def cpu_baseline(oracle, synth, case, cfg, budget_s=20.0):
     """The oracle as it stands, timed on the host cores over whole sequences of the same batch."""
     import numpy as np
@@ -82,6 +114,9 @@ def main():
     ap.add_argument("--waves-per-cu", type=int, default=0, help="persistent waves per compute unit (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the prefetch-off leg and the other workloads")
+    ap.add_argument("--layer-stack-only", type=int, default=0, metavar="LAYERS",
+                    help="run only the layer stack with this many layers and print its record (profiling aid)")
+    ap.add_argument("--cross-layer-touch", type=int, default=0)
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run plain 1 GiB device copies, so a counter run sees a copy kernel of known traffic")
     args = ap.parse_args()
@@ -130,6 +165,13 @@ def main():
         torch.cuda.empty_cache()
 
     pd_on = args.prefetch_distance if args.prefetch_distance is not None else 2
+    if args.layer_stack_only:
+        lms, lkvb, lwb, lcfg, L = layer_stack(kv, torch, synth, dev, args.steps, args.warmup, pd_on, args.cross_layer_touch,
+                                              layers=args.layer_stack_only)
+        print(json.dumps({"workload": lcfg["name"], "layers": L, "ms_per_pass": lms, "tokens_per_s": lcfg["B"] / (lms * 1e-3),
+                          "GB_per_s": (lkvb + lwb) / (lms * 1e-3) / 1e9, "prefetch_distance": pd_on,
+                          "cross_layer_touch": args.cross_layer_touch}), flush=True)
+        return
     log(f"[bench] workload {args.workload} prefetch_distance {pd_on}")
     cfg, cases, kvb, ms, main_ms = measure(args.workload, pd_on, args.steps, args.warmup)
     value = kvb / (ms * 1e-3) / 1e9
@@ -189,6 +231,21 @@ def main():
                                     "tokens_per_s": ocfg["B"] / (oms * 1e-3)}
             log(f"[bench] {ocfg['name']}: on {oms:.4f} ms, off {oms0:.4f} ms")
         result["other_workloads"] = others
+        # layer stack (configuration 4): tokens/s of 32 x (dense layer + attention), prefetch on / off, cross-layer touch
+        del cases
+        torch.cuda.empty_cache()
+        ls = {}
+        for name, pd_, cross in (("on", pd_on, 0), ("on_cross_layer_touch", pd_on, 1), ("off", 0, 0)):
+            lms, lkvb, lwb, lcfg, L = layer_stack(kv, torch, synth, dev, max(3, args.steps // 20), 2, pd_, cross)
+            torch.cuda.empty_cache()
+            ls[name] = {"ms_per_pass": lms, "tokens_per_s": lcfg["B"] / (lms * 1e-3), "GB_per_s": (lkvb + lwb) / (lms * 1e-3) / 1e9,
+                        "pct_hbm_peak": 100.0 * (lkvb + lwb) / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            log(f"[bench] layer stack {name}: {lms:.3f} ms/pass, {lcfg['B'] / (lms * 1e-3):.0f} tokens/s")
+        ls["layers"] = L
+        ls["kv_bytes_per_pass"] = lkvb
+        ls["weight_bytes_per_pass"] = lwb
+        result["layer_stack"] = ls
+        cfg, cases = make_cases(args.workload, copies=1)
 
     if not args.no_cpu_baseline:
         import oracle

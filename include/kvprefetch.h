@@ -85,10 +85,12 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
  * results do not depend on it.  The paper prefetches only inside the attention kernel
  * (next iteration, Section 3.1); the cross-layer form is this repository's harness.
  *
- *   x        [B, K] bf16 dense;  weights[l] [K, N] bf16 dense, N >= Hq*d;  gemm_out [B, N] bf16 dense
+ *   x        [B, K] bf16, rows dense;  gemm_out [B, N] bf16, rows dense, N >= Hq*d when q == NULL
+ *   weights[l] bf16, either [K, N] row-major or tile-packed [N/128, K, 128] (column tile t holds
+ *            W[:, 128t : 128t+128] as one contiguous K x 128 run: the form the kernel streams fastest)
  *   q, k_caches, v_caches, outs: arrays of num_layers tensor pointers (host arrays of
- *   host structs naming device memory).  Supported GEMM shapes: B <= 128 (or a multiple
- *   of 128), K % 64 == 0, N % 128 == 0.
+ *   host structs naming device memory).  Supported GEMM shapes: B <= 128, K % 128 == 0,
+ *   N % 128 == 0.
  */
 int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* const* weights,
                          kv_tensor* gemm_out, const kv_tensor* const* q,

@@ -20,5 +20,6 @@ from .binding import (  # noqa: F401
     kv_version,
     kv_last_error,
     load_library,
+    pack_weights,
     library_path,
 )

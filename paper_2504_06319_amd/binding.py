@@ -222,6 +222,14 @@ def kv_profile_read():
     return a.value, n.value
 
 
+def pack_weights(w: torch.Tensor) -> torch.Tensor:
+    """Re-lay a [K, N] weight matrix as [N/128, K, 128] (one contiguous run per 128-column tile); set-up time."""
+    K, N = w.shape
+    if N % 128:
+        raise KVError(1, "pack_weights: N must be a multiple of 128")
+    return w.reshape(K, N // 128, 128).permute(1, 0, 2).contiguous()
+
+
 def kv_block_bytes(elem_bytes: int, head_dim: int, block_size: int) -> int:
     return int(load_library().kv_block_bytes(elem_bytes, head_dim, block_size))
 

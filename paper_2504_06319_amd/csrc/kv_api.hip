@@ -260,16 +260,19 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
         const kv_tensor* w = weights[l];
         if (!w || !w->data || !k_caches[l] || !v_caches[l] || !outs[l] || (q && !q[l]))
             return fail(KV_ERR_INVALID, "kv_decode_layerstack: null tensor in layer %d", l);
-        if (w->ndim != 2 || w->dtype != KV_BF16 || w->shape[0] != K || w->shape[1] != N || w->stride[1] != 1 ||
-            ((uintptr_t)w->data) % 16 || w->stride[0] % 8)
-            return fail(KV_ERR_INVALID, "kv_decode_layerstack: weights[%d] must be dense bf16 [%lld, %lld]", l, (long long)K, (long long)N);
+        const bool row_major = w->ndim == 2 && w->shape[0] == K && w->shape[1] == N && w->stride[1] == 1 && w->stride[0] % 8 == 0;
+        const bool packed = w->ndim == 3 && w->shape[0] * 128 == N && w->shape[1] == K && w->shape[2] == 128 &&
+                            w->stride[2] == 1 && w->stride[1] % 8 == 0 && w->stride[0] % 8 == 0;
+        if (w->dtype != KV_BF16 || ((uintptr_t)w->data) % 16 || !(row_major || packed))
+            return fail(KV_ERR_INVALID, "kv_decode_layerstack: weights[%d] must be bf16 [%lld, %lld] row-major or [%lld, %lld, 128] tile-packed",
+                        l, (long long)K, (long long)N, (long long)(N / 128), (long long)K);
         if (outs[l]->ndim != 3) return fail(KV_ERR_INVALID, "kv_decode_layerstack: outs[%d] must have rank 3", l);
     }
     const int64_t B = outs[0]->shape[0], Hq = outs[0]->shape[1], d = outs[0]->shape[2];
     if (B != M) return fail(KV_ERR_INVALID, "kv_decode_layerstack: outs batch %lld differs from x rows %lld", (long long)B, (long long)M);
     if (!q && N < Hq * d) return fail(KV_ERR_INVALID, "kv_decode_layerstack: gemm_out has %lld columns, queries need %lld", (long long)N, (long long)(Hq * d));
-    if (M > 128 || K % 128 || K < 128 || N % 64 || N < 64)
-        return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: GEMM shape [%lld x %lld] . [%lld x %lld] not covered (rows <= 128, K %% 128 == 0, N %% 64 == 0)",
+    if (M > 128 || K % 128 || K < 128 || N % 128 || N < 128)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: GEMM shape [%lld x %lld] . [%lld x %lld] not covered (rows <= 128, K %% 128 == 0, N %% 128 == 0)",
                     (long long)M, (long long)K, (long long)K, (long long)N);
     hipStream_t main_stream = (hipStream_t)stream;
 
@@ -301,8 +304,11 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
             kvp::launch_touch_mfma(r.p, r.bs, kTouchTiles, (uint32_t*)r.p.partials, g_side_stream);
             (void)hipEventRecord(g_join_event, g_side_stream);
         }
-        const int grc = kvp::launch_layer_gemm(x->data, weights[l]->data, gemm_out->data, (int)M, (int)K, (int)N,
-                                               x->stride[0], weights[l]->stride[0], gemm_out->stride[0], main_stream);
+        const kv_tensor* wl = weights[l];
+        const int64_t ldw = wl->ndim == 2 ? wl->stride[0] : wl->stride[1];
+        const int64_t w_tile_stride = wl->ndim == 2 ? 128 : wl->stride[0];
+        const int grc = kvp::launch_layer_gemm(x->data, wl->data, gemm_out->data, (int)M, (int)K, (int)N, x->stride[0], ldw,
+                                               w_tile_stride, gemm_out->stride[0], main_stream);
         if (grc == -2) return fail(KV_ERR_HIP, "kv_decode_layerstack: could not raise the dynamic LDS limit of the GEMM kernel");
         if (grc != 0) return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: GEMM shape not covered");
         if (int rc = check_launch("kv_decode_layerstack GEMM kernel")) return rc;

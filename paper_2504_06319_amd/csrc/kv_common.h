@@ -96,8 +96,8 @@ int launch_attn_valu(const AttnParams& p, int elem, int d, int bs, hipStream_t s
 int launch_attn_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream);
 int launch_finalize_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream);
 int launch_touch_mfma(const AttnParams& p, int bs, int tiles, uint32_t* sink, hipStream_t stream);
-int launch_layer_gemm(const void* x, const void* w, void* y, int M, int K, int N, int64_t ldx, int64_t ldw, int64_t ldy,
-                      hipStream_t stream);
+int launch_layer_gemm(const void* x, const void* w, void* y, int M, int K, int N, int64_t ldx, int64_t ldw,
+                      int64_t w_tile_stride, int64_t ldy, hipStream_t stream);
 int mfma_worker_lds_bytes(int prefetch_distance);
 size_t mfma_partial_bytes(int num_workers, int G);
 constexpr int kMaxMfmaWorkers = 4096;
