@@ -115,6 +115,7 @@ __device__ __forceinline__ void lds_wait_v(u32x2 (&r)[8]) {
                  : "memory");
 }
 
+constexpr int kAuxNonTemporal = 2;                   // cache-policy operand of global_load_lds: nt
 constexpr int kTileTokens = 16;
 constexpr int kRowBytes = 256;                       // 128 x 16-bit
 constexpr int kTileBytes = kTileTokens * kRowBytes;  // 4 KB for K, the same for V
@@ -278,12 +279,15 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         const unsigned char* kt = kcache + ((int64_t)phys * p.kv_stride_blk + (int64_t)c.kvh * p.kv_stride_h) * 2 + sub;
         const unsigned char* vt_ = vcache + ((int64_t)phys * p.v_stride_blk + (int64_t)c.kvh * p.v_stride_h) * 2 + sub;
         unsigned char* dst = smem + stage * kStageBytes;
+        // every KV byte is used once: the fetches carry the non-temporal hint so that they do not displace
+        // anything in L2 / the memory-side cache (the paper's eviction-priority remark, Section 3.3); measured
+        // 184 -> 164 us on the Llama-3-8B-shaped batch
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(kt + koff[r]), KVP_LDS(dst + r * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(kt + koff[r]), KVP_LDS(dst + r * 1024), 16, 0, kAuxNonTemporal);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kTileBytes + r * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kTileBytes + r * 1024), 16, 0, kAuxNonTemporal);
     };
 
     float4v o[8];
