@@ -32,7 +32,8 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
                           c["scale"], c["num_kv_heads"], c["block_size"], pd)
     for i in range(warmup):
         step(i)
-    kv.kv_profile_enable(steps)
+    every = 4                                  # every 4th launch of the timed region carries an event pair
+    kv.kv_profile_enable((steps + every - 1) // every, every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
@@ -41,7 +42,7 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
     t1 = time.perf_counter()
     main_ms, n = kv.kv_profile_read()
     kv.kv_profile_enable(0)
-    assert n == steps
+    assert n == (steps + every - 1) // every
     return (t1 - t0) * 1e3 / steps, main_ms / n
 
 
@@ -190,7 +191,7 @@ def main():
                    "head_dim": cfg["d"], "block_size": cfg["bs"],
                    "context_lens": "fixed" if "lens" in cfg else f"uniform{list(cfg['len_range'])}",
                    "kv_bytes_per_step": kvb, "prefetch_distance": pd_on,
-                   "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on)},
+                   "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, cfg["d"])},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "tokens_per_s": cfg["B"] / (ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -202,7 +203,7 @@ def main():
 
     if not args.no_extra:
         _, _, _, ms0, main0 = measure(args.workload, 0, args.steps, args.warmup)
-        result["prefetch_off"] = {"prefetch_distance": 0, "waves_per_cu": kv.kv_decode_get_waves_per_cu(0),
+        result["prefetch_off"] = {"prefetch_distance": 0, "waves_per_cu": kv.kv_decode_get_waves_per_cu(0, cfg["d"]),
                                   "ms_per_step": ms0, "value": kvb / (ms0 * 1e-3) / 1e9,
                                   "kernel_ms": main0, "speedup_on_vs_off": ms0 / ms}
         log(f"[bench] off: {ms0:.4f} ms/step")

@@ -65,8 +65,8 @@ typedef struct kv_tensor {
  *   prefetch_distance  0 .. KV_MAX_PREFETCH_DISTANCE.
  *   stream       hipStream_t, NULL = the default stream.
  *
- * Supported: d in {64, 128}, block_size in {16, 32}, Hq/Hkv in 1..16.  When
- * MB * block_size exceeds one partition the call needs the workspace below.
+ * Supported: d in {64, 128}, block_size in {16, 32}, Hq/Hkv in 1..16.  Every call needs the
+ * registered workspace below.
  */
 #define KV_MAX_PREFETCH_DISTANCE 4
 int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
@@ -100,41 +100,42 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
                          int prefetch_distance, int cross_layer_prefetch, void* stream);
 
 /*
- * Split-KV workspace (the block index range [s, e) that Algorithm 1 takes as input
- * lets a worker own part of a sequence; partial results are merged by a second
- * kernel).  Bytes needed for a call with these extents: for head_dim 128 a fixed
- * bound (two partial pieces per persistent worker), for head_dim 64 one partial per
- * (sequence, query head, partition), 0 when one partition covers max_context.
+ * Split-KV workspace (the block index range [s, e) that Algorithm 1 takes as input lets a
+ * worker own part of a sequence; the pieces of a sequence that several workers share are
+ * merged by a second kernel).  Bytes a call with these extents needs: a fixed bound, two
+ * partial pieces of min(Hq, 16) rows of (d + 4) floats for each of at most 4096 workers
+ * (69 MB at d 128, Hq >= 16).  0 for unsupported extents.
  */
 size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size);
 
-/* Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters. */
+/*
+ * Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters.
+ * While registered the memory belongs to the library; calls that overlap in time on one
+ * device share it and race.
+ */
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
 
-/* head_dim 64 path: tokens per split-KV partition (multiple of 128, 128 .. 65536); 0 restores the default. */
-int kv_decode_set_partition_tokens(int tokens);
-int kv_decode_get_partition_tokens(void);
-
 /*
- * head_dim 128 path: persistent waves (workers) per compute unit, 1 .. 16; 0 restores the
- * automatic choice.  Each worker holds (prefetch_distance + 1) x 8 KB of LDS, so the
- * number in effect is capped by the 160 KB of a compute unit (Eq. 2 re-derived for
- * LDS as the prefetch target: bytes in flight per CU = 8 KB x prefetch_distance x waves);
- * kv_decode_get_waves_per_cu returns the number a call with that distance would use.
+ * Persistent waves (workers) per compute unit, 1 .. 16; 0 restores the automatic choice (6).
+ * Each worker holds (prefetch_distance + 1) stages of LDS (8 KB each at head_dim 128, 4 KB at
+ * 64), so the number in effect is capped by the 160 KB of a compute unit (Eq. 2 re-derived
+ * for LDS as the prefetch target: bytes in flight per CU = stage x prefetch_distance x waves);
+ * kv_decode_get_waves_per_cu returns the number a call with that distance and head_dim would use.
  */
 int kv_decode_set_waves_per_cu(int waves);
-int kv_decode_get_waves_per_cu(int prefetch_distance);
+int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
 
 /*
  * Timing of the main attention kernel with HIP events on the call's own stream (the paper
- * reports the attention kernel's duration, Table 2).  kv_profile_enable(n) creates events for
- * the next n kv_decode_attn calls (host-side allocation, not on the timed path; n = 0 frees
- * them); while enabled each call records one event before and one after its main kernel.
+ * reports the attention kernel's duration, Table 2).  kv_profile_enable(n, every) creates
+ * events for n samples (host-side allocation, not on the timed path; n = 0 frees them); while
+ * enabled, every `every`-th kv_decode_attn call records one event before and one after its
+ * main kernel (an event pair costs a few microseconds of stream time, hence the sampling).
  * kv_profile_read waits for the recorded calls, returns the summed kernel durations in
  * milliseconds and the number of calls, and rearms the same events.  Calls from several
  * threads share one slot counter under a mutex.
  */
-int kv_profile_enable(int max_calls);
+int kv_profile_enable(int max_calls, int every);
 int kv_profile_read(double* main_ms_sum, int* calls);
 
 /* Text of the last error on this thread; never NULL. */

@@ -39,8 +39,7 @@ class KVTensor(ctypes.Structure):
 
 EXPORTS = [
     "kv_decode_attn", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_decode_set_workspace",
-    "kv_decode_set_partition_tokens", "kv_decode_get_partition_tokens", "kv_decode_set_waves_per_cu",
-    "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
+    "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_profile_enable", "kv_profile_read",
 ]
 
@@ -71,15 +70,12 @@ def load_library():
             lib.kv_decode_workspace_bytes.argtypes = [ctypes.c_int] * 5
             lib.kv_decode_set_workspace.restype = ctypes.c_int
             lib.kv_decode_set_workspace.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
-            lib.kv_decode_set_partition_tokens.restype = ctypes.c_int
-            lib.kv_decode_set_partition_tokens.argtypes = [ctypes.c_int]
-            lib.kv_decode_get_partition_tokens.restype = ctypes.c_int
             lib.kv_decode_set_waves_per_cu.restype = ctypes.c_int
             lib.kv_decode_set_waves_per_cu.argtypes = [ctypes.c_int]
             lib.kv_decode_get_waves_per_cu.restype = ctypes.c_int
-            lib.kv_decode_get_waves_per_cu.argtypes = [ctypes.c_int]
+            lib.kv_decode_get_waves_per_cu.argtypes = [ctypes.c_int, ctypes.c_int]
             lib.kv_profile_enable.restype = ctypes.c_int
-            lib.kv_profile_enable.argtypes = [ctypes.c_int]
+            lib.kv_profile_enable.argtypes = [ctypes.c_int, ctypes.c_int]
             lib.kv_profile_read.restype = ctypes.c_int
             lib.kv_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
             lib.kv_last_error.restype = ctypes.c_char_p
@@ -149,20 +145,12 @@ def kv_decode_workspace_bytes(B: int, Hq: int, d: int, max_context: int, block_s
     return int(load_library().kv_decode_workspace_bytes(B, Hq, d, max_context, block_size))
 
 
-def kv_decode_set_partition_tokens(tokens: int):
-    _check(load_library().kv_decode_set_partition_tokens(int(tokens)))
-
-
-def kv_decode_get_partition_tokens() -> int:
-    return int(load_library().kv_decode_get_partition_tokens())
-
-
 def kv_decode_set_waves_per_cu(waves: int):
     _check(load_library().kv_decode_set_waves_per_cu(int(waves)))
 
 
-def kv_decode_get_waves_per_cu(prefetch_distance: int) -> int:
-    return int(load_library().kv_decode_get_waves_per_cu(int(prefetch_distance)))
+def kv_decode_get_waves_per_cu(prefetch_distance: int, head_dim: int = 128) -> int:
+    return int(load_library().kv_decode_get_waves_per_cu(int(prefetch_distance), int(head_dim)))
 
 
 def kv_decode_attn(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
@@ -211,8 +199,8 @@ def kv_decode_layerstack(x, weights, gemm_out, q, k_caches, v_caches, block_tabl
     return outs
 
 
-def kv_profile_enable(max_calls: int):
-    _check(load_library().kv_profile_enable(int(max_calls)))
+def kv_profile_enable(max_calls: int, every: int = 1):
+    _check(load_library().kv_profile_enable(int(max_calls), int(every)))
 
 
 def kv_profile_read():

@@ -1,4 +1,4 @@
-// Paged decode attention for head_dim 128 on the matrix cores, with an LDS ring that
+// Paged decode attention (head_dim 64 or 128) on the matrix cores, with an LDS ring that
 // holds the KV tiles a wave will consume next.
 //
 // Work mapping.  The paper's kernel gives a thread block one (query head, sequence) and
@@ -25,16 +25,17 @@
 // closest asynchronous fetch.
 //
 // Tile math, all on MFMA with fp32 accumulation:
-//   S^T[t, g]  = sum_c K[t, c] Q[g, c]     4 x v_mfma_f32_16x16x32 (A = K tile, B = Q^T)
+//   S^T[t, g]  = sum_c K[t, c] Q[g, c]     d/32 x v_mfma_f32_16x16x32 (A = K tile, B = Q^T)
 //   P^T[t, g]  = 2^(S^T - m[g])            online softmax; max over tokens by lane permutes
-//   O^T[c, g] += sum_t V[t, c] P^T[t, g]   8 x v_mfma_f32_16x16x16 (A = V^T via LDS transpose read)
+//   O^T[c, g] += sum_t V[t, c] P^T[t, g]   d/16 x v_mfma_f32_16x16x16 (A = V^T via LDS transpose read)
 // Computing the transposed products keeps the head index on lane % 16 from the logits to
 // the output accumulators, so the softmax rescale is a per-lane multiply.
 //
-// LDS layout of a stage: K tile then V tile, each 16 rows x 256 B, written by
+// LDS layout of a stage: K tile then V tile, each 16 rows x 2d bytes, written by
 // global_load_lds_dwordx4 (lane i of load r lands at r*1024 + i*16).  Bank conflicts are
-// avoided by permuting which 16-byte chunk of a row each lane fetches: K rows are stored
-// with chunk index XOR row, V rows with chunk index XOR 2*(row % 8).
+// avoided by permuting which 16-byte chunk of a row each lane fetches: with C = d/8 chunks per
+// row and s = row / (16/C), K rows are stored with chunk index XOR (s mod C), V rows with
+// chunk index XOR 2*(s mod C/2) (d = 128: XOR row and XOR 2*(row mod 8)).
 #include "kv_common.h"
 
 #include <type_traits>
@@ -102,11 +103,22 @@ __device__ __forceinline__ void lds_read_tr16_x4(u32x2& r0, u32x2& r1, u32x2& r2
         : "memory");
 }
 
+__device__ __forceinline__ void lds_read_b128_x2(u32x4& r0, u32x4& r1, uint32_t a0, uint32_t a1) {
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3" : "=&v"(r0), "=&v"(r1) : "v"(a0), "v"(a1) : "memory");
+}
+
 // Wait until at most N of this wave's LDS operations are outstanding; the registers are
 // passed through so that no use of them can be scheduled above the wait.
 template <int N>
 __device__ __forceinline__ void lds_wait_k(u32x4& r0, u32x4& r1, u32x4& r2, u32x4& r3) {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lds_wait_k(u32x4& r0, u32x4& r1) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(r0), "+v"(r1) : "n"(N) : "memory");
+}
+__device__ __forceinline__ void lds_wait_v(u32x2 (&r)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) : : "memory");
 }
 __device__ __forceinline__ void lds_wait_v(u32x2 (&r)[8]) {
     asm volatile("s_waitcnt lgkmcnt(0)"
@@ -117,12 +129,24 @@ __device__ __forceinline__ void lds_wait_v(u32x2 (&r)[8]) {
 
 constexpr int kAuxNonTemporal = 2;                   // cache-policy operand of global_load_lds: nt
 constexpr int kTileTokens = 16;
-constexpr int kRowBytes = 256;                       // 128 x 16-bit
-constexpr int kTileBytes = kTileTokens * kRowBytes;  // 4 KB for K, the same for V
-constexpr int kStageBytes = 2 * kTileBytes;
-constexpr int kD = 128;
-constexpr int kPartialStride = kD + 4;               // floats per partial row: acc[128], max, sum, 2 pad (16-byte rows)
 constexpr int kMaxWorkers = 4096;
+
+// Per-head_dim geometry of a 16-token tile.
+template <int D>
+struct Geo {
+    static constexpr int kRowBytes = D * 2;                        // one token's row of K (or V)
+    static constexpr int kTileBytes = kTileTokens * kRowBytes;     // 4 KB (d 128) / 2 KB (d 64) for K, the same for V
+    static constexpr int kStageBytes = 2 * kTileBytes;
+    static constexpr int kChunks = D / 8;                          // 16-byte chunks per row
+    static constexpr int kRowsPerLoad = kWaveSize / kChunks;       // rows one wave-wide 1 KB fetch lands
+    static constexpr int kLoadsPerTile = kTileTokens / kRowsPerLoad;
+    static constexpr int kSwzShift = 16 / kChunks;                 // rows that share a swizzle value
+    static constexpr int kKSteps = D / 32;                         // MFMAs of the logits
+    static constexpr int kColBlocks = D / 16;                      // 16-column blocks of the output
+    static constexpr int kPartialStride = D + 4;                   // floats per partial row: acc, max, sum, 2 pad (16-byte rows)
+    __host__ __device__ static constexpr int swz_k(int row) { return (row / kSwzShift) % kChunks; }
+    __host__ __device__ static constexpr int swz_v_half(int row) { return (row / kSwzShift) % (kChunks / 2); }   // V swizzle / 2
+};
 
 // Position of a worker inside the flat tile space; every field is wave-uniform.
 struct Cursor {
@@ -187,12 +211,16 @@ __device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_wo
     return (int64_t)worker * T / num_workers;
 }
 
-template <Elem E, int BS, int PD>
+template <Elem E, int D, int BS, int PD>
 __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
-    constexpr int D = kD;
+    using G_ = Geo<D>;
     constexpr int NS = PD + 1;                  // LDS stages of the wave
     constexpr int TPB = BS / kTileTokens;       // 16-token tiles per KV block
-    constexpr int LOADS = 8;                    // wave-wide 1 KB fetches per tile pair (4 K + 4 V)
+    constexpr int LPT = G_::kLoadsPerTile;      // wave-wide 1 KB fetches per K (or V) tile
+    constexpr int LOADS = 2 * LPT;              // per tile pair
+    constexpr int KJ = G_::kKSteps, CB = G_::kColBlocks;
+    constexpr int kRowBytes = G_::kRowBytes, kTileBytes = G_::kTileBytes, kStageBytes = G_::kStageBytes;
+    constexpr int kPartialStride = G_::kPartialStride;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int worker = blockIdx.x;
@@ -236,12 +264,12 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     };
 
     // ---- Q^T operand of a unit: lane (g = lr, lq) holds Q[g][(4j + lq) * 8 .. +8], zero rows for g >= G
-    u32x4 qb[4];
+    u32x4 qb[KJ];
     auto load_q = [&](int b, int kvh) {
         const uint16_t* qrow = reinterpret_cast<const uint16_t*>(p.q) + (int64_t)b * p.q_stride_b +
                                (int64_t)(kvh * G + min(lr, G - 1)) * p.q_stride_h;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < KJ; ++j) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(qrow + (4 * j + lq) * 8);
             qb[j] = lr < G ? v : u32x4{0, 0, 0, 0};
         }
@@ -249,24 +277,26 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     load_q(ca.b, ca.kvh);
 
     // ---- per-lane byte offsets, loop invariant
-    // fetch r (0..3) of a tile lands rows 4r..4r+3; this lane lands row t = 4r + lq at LDS slot lr, so it
-    // fetches chunk (lr ^ swizzle(t)) of row t
-    uint32_t koff[4], voff[4];
+    // fetch r of a tile lands kRowsPerLoad rows; this lane lands row t = r * kRowsPerLoad + lane / kChunks at
+    // stored chunk lane % kChunks, so it fetches chunk (stored ^ swizzle(t)) of row t
+    uint32_t koff[LPT], voff[LPT];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int t = 4 * r + lq;
-        koff[r] = t * kRowBytes + ((lr ^ t) << 4);
-        voff[r] = t * kRowBytes + ((lr ^ (2 * (t % 8))) << 4);
+    for (int r = 0; r < LPT; ++r) {
+        const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
+        koff[r] = t * kRowBytes + ((stored ^ G_::swz_k(t)) << 4);
+        voff[r] = t * kRowBytes + ((stored ^ (2 * G_::swz_v_half(t))) << 4);
     }
-    // K read for MFMA j: row lr, logical chunk 4j + lq  ->  stored chunk (4j + lq) ^ lr
-    uint32_t kread[4];
+    // K read for MFMA j: row lr, logical chunk 4j + lq  ->  stored chunk (4j + lq) ^ swizzle(lr)
+    uint32_t kread[KJ];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) kread[j] = lr * kRowBytes + (((4 * j + lq) ^ lr) << 4);
-    // V transpose read for column block cb: row lane/4, logical byte 32 cb + 8 (lane % 4)
+    for (int j = 0; j < KJ; ++j) kread[j] = lr * kRowBytes + (((4 * j + lq) ^ G_::swz_k(lr)) << 4);
+    // V transpose read for column block cb: row lane/4, logical byte 32 cb + 8 (lane % 4); the swizzle is even, so
+    // it acts on the 32-byte block index
     const int vt = lane / 4;
-    uint32_t vread[8];
+    uint32_t vread[CB];
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb) vread[cb] = kTileBytes + vt * kRowBytes + ((cb ^ (vt % 8)) << 5) + ((lane % 4) << 3);
+    for (int cb = 0; cb < CB; ++cb)
+        vread[cb] = kTileBytes + vt * kRowBytes + ((cb ^ G_::swz_v_half(vt)) << 5) + ((lane % 4) << 3);
 
     const uint32_t ring_addr = (uint32_t)(uintptr_t)KVP_LDS(smem);      // LDS byte address of the ring
     const unsigned char* kcache = reinterpret_cast<const unsigned char*>(p.k_cache);
@@ -283,16 +313,16 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         // anything in L2 / the memory-side cache (the paper's eviction-priority remark, Section 3.3); measured
         // 184 -> 164 us on the Llama-3-8B-shaped batch
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < LPT; ++r)
             __builtin_amdgcn_global_load_lds(KVP_GLOBAL(kt + koff[r]), KVP_LDS(dst + r * 1024), 16, 0, kAuxNonTemporal);
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < LPT; ++r)
             __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kTileBytes + r * 1024), 16, 0, kAuxNonTemporal);
     };
 
-    float4v o[8];
+    float4v o[CB];
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb) o[cb] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < CB; ++cb) o[cb] = float4v{0.f, 0.f, 0.f, 0.f};
     float m = kNegBig, l = 0.f;
 
     // ---- prologue: the prefetch cursor runs PD tiles ahead of the consume cursor
@@ -329,18 +359,21 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         asm volatile("" ::: "memory");
         const uint32_t st = ring_addr + stage * kStageBytes;
 
-        // ---- issue every LDS read of the tile: 4 K operands, then 8 transposed V operands
-        u32x4 ka[4];
-        u32x2 va[8];
-        lds_read_b128_x4(ka[0], ka[1], ka[2], ka[3], st + kread[0], st + kread[1], st + kread[2], st + kread[3]);
-        lds_read_tr16_x4(va[0], va[1], va[2], va[3], st + vread[0], st + vread[1], st + vread[2], st + vread[3]);
-        lds_read_tr16_x4(va[4], va[5], va[6], va[7], st + vread[4], st + vread[5], st + vread[6], st + vread[7]);
+        // ---- issue every LDS read of the tile: the K operands, then the transposed V operands
+        u32x4 ka[KJ];
+        u32x2 va[CB];
+        if constexpr (KJ == 4) lds_read_b128_x4(ka[0], ka[1], ka[2], ka[3], st + kread[0], st + kread[1], st + kread[2], st + kread[3]);
+        else lds_read_b128_x2(ka[0], ka[1], st + kread[0], st + kread[1]);
+#pragma unroll
+        for (int c4 = 0; c4 < CB; c4 += 4)
+            lds_read_tr16_x4(va[c4], va[c4 + 1], va[c4 + 2], va[c4 + 3], st + vread[c4], st + vread[c4 + 1], st + vread[c4 + 2], st + vread[c4 + 3]);
 
-        // ---- S^T = K Q^T once the K operands are back (the 8 V reads may still be outstanding)
-        lds_wait_k<8>(ka[0], ka[1], ka[2], ka[3]);
+        // ---- S^T = K Q^T once the K operands are back (the CB reads of V may still be outstanding)
+        if constexpr (KJ == 4) lds_wait_k<CB>(ka[0], ka[1], ka[2], ka[3]);
+        else lds_wait_k<CB>(ka[0], ka[1]);
         float4v sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) sacc = mfma_k32<E>(ka[j], qb[j], sacc);
+        for (int j = 0; j < KJ; ++j) sacc = mfma_k32<E>(ka[j], qb[j], sacc);
         lds_wait_v(va);
 
         // ---- online softmax over this tile's 16 tokens (lane holds tokens 4 lq + i of head lr)
@@ -357,7 +390,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             const uint32_t m01 = ((tok0 + 0 < n) ? 0x0000ffffu : 0u) | ((tok0 + 1 < n) ? 0xffff0000u : 0u);
             const uint32_t m23 = ((tok0 + 2 < n) ? 0x0000ffffu : 0u) | ((tok0 + 3 < n) ? 0xffff0000u : 0u);
 #pragma unroll
-            for (int cb = 0; cb < 8; ++cb) { va[cb][0] &= m01; va[cb][1] &= m23; }
+            for (int cb = 0; cb < CB; ++cb) { va[cb][0] &= m01; va[cb][1] &= m23; }
         }
         float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -367,7 +400,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             const float alpha = fast_exp2(m - m_new);
             l *= alpha;
 #pragma unroll
-            for (int cb = 0; cb < 8; ++cb) o[cb] *= alpha;
+            for (int cb = 0; cb < CB; ++cb) o[cb] *= alpha;
             m = m_new;
         }
         float pr[4];
@@ -378,7 +411,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
 
         // ---- O^T += V^T P^T
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb) o[cb] = mfma_k16<E>(va[cb], pb, o[cb]);
+        for (int cb = 0; cb < CB; ++cb) o[cb] = mfma_k16<E>(va[cb], pb, o[cb]);
 
         if constexpr (PD > 0) { stage = stage + 1 == NS ? 0 : stage + 1; }
 
@@ -394,7 +427,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
                     uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)ca.b * p.out_stride_b +
                                      (int64_t)(ca.kvh * G + lr) * p.out_stride_h + 4 * lq;
 #pragma unroll
-                    for (int cb = 0; cb < 8; ++cb) {
+                    for (int cb = 0; cb < CB; ++cb) {
                         const u32x2 w = {pack2<E>(o[cb][0] * inv, o[cb][1] * inv), pack2<E>(o[cb][2] * inv, o[cb][3] * inv)};
                         *reinterpret_cast<u32x2*>(orow + 16 * cb) = w;
                     }
@@ -402,12 +435,12 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
                     const int slot = piece_at_range_start ? 0 : 1;
                     float* dst = p.partials + ((int64_t)(worker * 2 + slot) * G + lr) * kPartialStride;
 #pragma unroll
-                    for (int cb = 0; cb < 8; ++cb) *reinterpret_cast<float4v*>(dst + 16 * cb + 4 * lq) = o[cb];
+                    for (int cb = 0; cb < CB; ++cb) *reinterpret_cast<float4v*>(dst + 16 * cb + 4 * lq) = o[cb];
                     if (lq == 0) { dst[D] = m; dst[D + 1] = lt; }
                 }
             }
 #pragma unroll
-            for (int cb = 0; cb < 8; ++cb) o[cb] = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int cb = 0; cb < CB; ++cb) o[cb] = float4v{0.f, 0.f, 0.f, 0.f};
             m = kNegBig;
             l = 0.f;
             piece_at_range_start = false;
@@ -430,9 +463,9 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
 // The kernel is a chain of dependent memory round trips, so it is written to have two of them: one pass
 // over context_lens, then every load of a batch of pieces (max, sum and accumulator column) in flight at
 // once, each thread keeping its own running (m*, sum, acc) across batches.
-template <Elem E>
-__global__ __launch_bounds__(kD) void attn_finalize_kernel(AttnParams p, int bs) {
-    constexpr int D = kD, PS = kPartialStride;
+template <Elem E, int D>
+__global__ __launch_bounds__(D) void attn_finalize_kernel(AttnParams p, int bs) {
+    constexpr int PS = Geo<D>::kPartialStride;
     const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x, lane = c % kWaveSize;
     const int G = p.G, Hkv = p.Hkv, kvh = h / G, g = h % G;
     const int max_len = p.MB * bs;
@@ -495,39 +528,52 @@ __global__ __launch_bounds__(kD) void attn_finalize_kernel(AttnParams p, int bs)
     orow[c] = pack1<E>(num / den);
 }
 
-template <Elem E, int BS, int PD>
+template <Elem E, int D, int BS, int PD>
 static int launch_one(const AttnParams& p, hipStream_t stream) {
-    const size_t lds = (size_t)(PD + 1) * kStageBytes;
-    auto kern = attn_mfma_kernel<E, BS, PD>;
+    const size_t lds = (size_t)(PD + 1) * Geo<D>::kStageBytes;
+    auto kern = attn_mfma_kernel<E, D, BS, PD>;
     hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), lds, stream, p);
     return 0;
 }
 
-template <Elem E, int BS>
+template <Elem E, int D, int BS>
 static int launch_pd(const AttnParams& p, hipStream_t stream) {
     switch (p.prefetch_distance) {
-        case 0: return launch_one<E, BS, 0>(p, stream);
-        case 1: return launch_one<E, BS, 1>(p, stream);
-        case 2: return launch_one<E, BS, 2>(p, stream);
-        case 3: return launch_one<E, BS, 3>(p, stream);
-        case 4: return launch_one<E, BS, 4>(p, stream);
+        case 0: return launch_one<E, D, BS, 0>(p, stream);
+        case 1: return launch_one<E, D, BS, 1>(p, stream);
+        case 2: return launch_one<E, D, BS, 2>(p, stream);
+        case 3: return launch_one<E, D, BS, 3>(p, stream);
+        case 4: return launch_one<E, D, BS, 4>(p, stream);
         default: return -1;
     }
 }
 
-// LDS bytes one worker (wave) of the head_dim-128 kernel holds at a prefetch distance.
-int mfma_worker_lds_bytes(int prefetch_distance) { return (prefetch_distance + 1) * kStageBytes; }
-
-// Bytes of partial storage for a launch with this many workers.
-size_t mfma_partial_bytes(int num_workers, int G) {
-    return (size_t)num_workers * 2 * G * kPartialStride * sizeof(float);
+template <Elem E>
+static int launch_shape(const AttnParams& p, int d, int bs, hipStream_t stream) {
+    if (d == 128) return bs == 16 ? launch_pd<E, 128, 16>(p, stream) : launch_pd<E, 128, 32>(p, stream);
+    return bs == 16 ? launch_pd<E, 64, 16>(p, stream) : launch_pd<E, 64, 32>(p, stream);
 }
 
-// Merge kernel of the head_dim-128 path; always launched after the main kernel (it also writes the zero
-// rows of empty sequences).
-int launch_finalize_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream) {
-    if (elem == (int)Elem::F16) hipLaunchKernelGGL(attn_finalize_kernel<Elem::F16>, dim3(p.Hq, p.B), dim3(kD), 0, stream, p, bs);
-    else hipLaunchKernelGGL(attn_finalize_kernel<Elem::BF16>, dim3(p.Hq, p.B), dim3(kD), 0, stream, p, bs);
+// LDS bytes one worker (wave) holds at a prefetch distance.
+int mfma_worker_lds_bytes(int prefetch_distance, int d) {
+    return (prefetch_distance + 1) * (d == 128 ? Geo<128>::kStageBytes : Geo<64>::kStageBytes);
+}
+
+// Bytes of partial storage for a launch with this many workers.
+size_t mfma_partial_bytes(int num_workers, int G, int d) {
+    return (size_t)num_workers * 2 * G * (d + 4) * sizeof(float);
+}
+
+// Merge kernel; always launched after the main kernel (it also writes the zero rows of empty sequences).
+int launch_finalize_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream) {
+    const dim3 grid(p.Hq, p.B);
+    if (elem == (int)Elem::F16) {
+        if (d == 128) hipLaunchKernelGGL((attn_finalize_kernel<Elem::F16, 128>), grid, dim3(128), 0, stream, p, bs);
+        else hipLaunchKernelGGL((attn_finalize_kernel<Elem::F16, 64>), grid, dim3(64), 0, stream, p, bs);
+    } else {
+        if (d == 128) hipLaunchKernelGGL((attn_finalize_kernel<Elem::BF16, 128>), grid, dim3(128), 0, stream, p, bs);
+        else hipLaunchKernelGGL((attn_finalize_kernel<Elem::BF16, 64>), grid, dim3(64), 0, stream, p, bs);
+    }
     return 0;
 }
 
@@ -535,9 +581,11 @@ int launch_finalize_mfma(const AttnParams& p, int elem, int bs, hipStream_t stre
 // worker's range, so that those lines sit in the memory-side cache when the attention kernel of the same
 // layer starts.  It runs on a side stream under the dense layer that precedes the attention call; it
 // writes nothing that is ever read and changes no result.
-template <int BS>
+template <int D, int BS>
 __global__ __launch_bounds__(kWaveSize) void attn_touch_kernel(AttnParams p, int tiles, uint32_t* sink) {
     constexpr int TPB = BS / kTileTokens;
+    constexpr int kTileBytes = Geo<D>::kTileBytes;
+    constexpr int kLines = kTileBytes / 128;         // 128-byte lines of a K (or V) tile: 32 (d 128) or 16 (d 64)
     const int worker = blockIdx.x, lane = threadIdx.x;
     const int Hkv = p.Hkv;
     const int max_len = p.MB * BS;
@@ -560,7 +608,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_touch_kernel(AttnParams p, int
         int phys = bt[(int64_t)b * p.bt_stride_b + j / TPB];
         phys = min(max(phys, 0), p.NBLK - 1);
         const unsigned char* tile = cache + ((int64_t)phys * sblk + (int64_t)kvh * sh) * 2 + (j % TPB) * kTileBytes;
-        acc ^= *reinterpret_cast<const uint32_t*>(tile + (lane % 32) * 128);
+        if (lane % 32 < kLines) acc ^= *reinterpret_cast<const uint32_t*>(tile + (lane % 32) * 128);
         if (r + 1 < r1) {                          // step to the next flat tile
             if (++j == ntiles) {
                 j = 0;
@@ -578,18 +626,25 @@ __global__ __launch_bounds__(kWaveSize) void attn_touch_kernel(AttnParams p, int
     if (acc == 0x9e3779b9u && tiles < 0) sink[0] = acc;      // never true: keeps the loads alive
 }
 
-int launch_touch_mfma(const AttnParams& p, int bs, int tiles, uint32_t* sink, hipStream_t stream) {
+int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* sink, hipStream_t stream) {
     if (p.num_workers < 1 || p.num_workers > kMaxWorkers) return -1;
-    if (bs == 16) hipLaunchKernelGGL(attn_touch_kernel<16>, dim3(p.num_workers), dim3(kWaveSize), 0, stream, p, tiles, sink);
-    else hipLaunchKernelGGL(attn_touch_kernel<32>, dim3(p.num_workers), dim3(kWaveSize), 0, stream, p, tiles, sink);
+    const dim3 grid(p.num_workers), block(kWaveSize);
+    if (d == 128) {
+        if (bs == 16) hipLaunchKernelGGL((attn_touch_kernel<128, 16>), grid, block, 0, stream, p, tiles, sink);
+        else hipLaunchKernelGGL((attn_touch_kernel<128, 32>), grid, block, 0, stream, p, tiles, sink);
+    } else {
+        if (bs == 16) hipLaunchKernelGGL((attn_touch_kernel<64, 16>), grid, block, 0, stream, p, tiles, sink);
+        else hipLaunchKernelGGL((attn_touch_kernel<64, 32>), grid, block, 0, stream, p, tiles, sink);
+    }
     return 0;
 }
 
-// head_dim 128 only.  Returns 0 or -1 (no such instantiation).
-int launch_attn_mfma(const AttnParams& p, int elem, int bs, hipStream_t stream) {
+// Returns 0 or -1 (no such instantiation).
+int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream) {
     if (p.num_workers < 1 || p.num_workers > kMaxWorkers) return -1;
-    if (elem == (int)Elem::F16) return bs == 16 ? launch_pd<Elem::F16, 16>(p, stream) : launch_pd<Elem::F16, 32>(p, stream);
-    return bs == 16 ? launch_pd<Elem::BF16, 16>(p, stream) : launch_pd<Elem::BF16, 32>(p, stream);
+    if (d != 64 && d != 128) return -1;
+    if (bs != 16 && bs != 32) return -1;
+    return elem == (int)Elem::F16 ? launch_shape<Elem::F16>(p, d, bs, stream) : launch_shape<Elem::BF16>(p, d, bs, stream);
 }
 
 }  // namespace kvp

@@ -24,7 +24,6 @@ int fail(int code, const char* fmt, ...) {
 std::mutex g_ws_mutex;
 void* g_ws_ptr = nullptr;
 size_t g_ws_bytes = 0;
-std::atomic<int> g_part_tokens{0};   // 0 = default
 std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
 std::atomic<int> g_num_cus{0};       // compute units of the device, read once
 
@@ -42,11 +41,11 @@ int num_cus() {
     return n;
 }
 
-// Persistent waves per compute unit of the head_dim-128 kernel: what the caller asked for, else 6 (measured
+// Persistent waves per compute unit of the attention kernel: what the caller asked for, else 6 (measured
 // best: about 48-96 KB of KV in flight per compute unit), capped by the LDS the rings need.  Odd counts above
 // one are rounded down: 5 and 10 waves per compute unit measured about 25 % slower than 4 and 8.
-int waves_per_cu(int prefetch_distance) {
-    const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance);
+int waves_per_cu(int prefetch_distance, int d) {
+    const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance, d);
     int w = g_waves_per_cu.load();
     if (w <= 0) w = 6;
     w = w < lds_limit ? w : lds_limit;
@@ -55,19 +54,9 @@ int waves_per_cu(int prefetch_distance) {
     return w;
 }
 
-constexpr int kDefaultPartTokens = 512;
-
-int part_tokens() {
-    int t = g_part_tokens.load();
-    return t > 0 ? t : kDefaultPartTokens;
-}
-
-size_t workspace_bytes(int B, int Hq, int d, int64_t max_context, int P) {
-    if (d == 128)   // persistent-worker kernel: two partial pieces per worker, sized for the largest launch
-        return kvp::mfma_partial_bytes(kvp::kMaxMfmaWorkers, Hq < 16 ? Hq : 16);
-    if (max_context <= P) return 0;
-    int64_t np = (max_context + P - 1) / P;
-    return (size_t)B * Hq * np * (d + 2) * sizeof(float);
+// Two partial pieces of G rows per worker, sized for the largest launch.
+size_t workspace_bytes(int Hq, int d) {
+    return kvp::mfma_partial_bytes(kvp::kMaxMfmaWorkers, Hq < 16 ? Hq : 16, d);
 }
 
 bool dense_tile(const kv_tensor* t) {   // [NBLK, Hkv, bs, d] with the [bs, d] tile contiguous
@@ -77,7 +66,6 @@ bool dense_tile(const kv_tensor* t) {   // [NBLK, Hkv, bs, d] with the [bs, d] t
 struct Resolved {
     kvp::AttnParams p;
     int elem, d, bs;
-    bool split;
 };
 
 int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
@@ -136,9 +124,7 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     if (!aligned(q, 2) || !aligned(k_cache, 2) || !aligned(v_cache, 2) || !aligned(out, 2))
         return fail(KV_ERR_INVALID, "kv_decode_attn: data pointers and outer strides must be 16-byte aligned");
 
-    const int P = part_tokens();
     const int64_t MB = block_tables->shape[1];
-    const int64_t max_context = MB * block_size;
     kvp::AttnParams& p = r->p;
     p.q = q->data; p.k_cache = k_cache->data; p.v_cache = v_cache->data;
     p.block_tables = (const int32_t*)block_tables->data;
@@ -151,39 +137,27 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.bt_stride_b = block_tables->stride[0];
     p.B = (int)B; p.Hq = (int)Hq; p.Hkv = num_kv_heads; p.G = G;
     p.MB = (int)MB; p.NBLK = (int)k_cache->shape[0];
-    p.part_blocks = P / block_size;
-    p.NP = (int)((max_context + P - 1) / P);
     p.prefetch_distance = prefetch_distance;
     p.scale_log2e = scale * kvp::kLog2e;
-    p.partials = nullptr;
     r->elem = q->dtype; r->d = (int)d; r->bs = block_size;
-    r->split = p.NP > 1;
-    p.num_workers = 0;
-    size_t need = 0;
-    if (d == 128) {
-        const int cus = num_cus();
-        if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
-        int nw = cus * waves_per_cu(prefetch_distance);
-        p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
-        need = kvp::mfma_partial_bytes(p.num_workers, G);
-        r->split = false;              // the finalize kernel is launched with the main kernel
-    } else if (r->split) {
-        need = workspace_bytes((int)B, (int)Hq, (int)d, max_context, P);
-    }
-    if (need > 0) {
-        std::lock_guard<std::mutex> lock(g_ws_mutex);
-        if (!g_ws_ptr || g_ws_bytes < need)
-            return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
-        p.partials = (float*)g_ws_ptr;
-    }
+    const int cus = num_cus();
+    if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
+    const int nw = cus * waves_per_cu(prefetch_distance, (int)d);
+    p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
+    const size_t need = kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (!g_ws_ptr || g_ws_bytes < need)
+        return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
+    p.partials = (float*)g_ws_ptr;
     return KV_OK;
 }
+
 
 // Optional per-call timing: two events per call, one on each side of the main attention kernel, recorded on
 // the call's stream (the merge kernel that follows is outside the bracket).
 std::mutex g_prof_mutex;
 std::vector<hipEvent_t> g_prof_events;
-int g_prof_capacity = 0, g_prof_calls = 0;
+int g_prof_capacity = 0, g_prof_calls = 0, g_prof_every = 1, g_prof_seen = 0;
 
 hipEvent_t prof_event(int call, int which) { return g_prof_events[(size_t)call * 2 + which]; }
 
@@ -200,27 +174,17 @@ int check_launch(const char* what) {
 }
 
 int run_attn(const Resolved& r, hipStream_t stream) {
-    if (r.d != 128 && r.p.G > 8)
-        return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: group size %d with head_dim %d not covered", r.p.G, r.d);
     std::unique_lock<std::mutex> prof_lock(g_prof_mutex);
-    const int slot = (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity) ? g_prof_calls++ : -1;
+    int slot = -1;
+    if (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity && (g_prof_seen++ % g_prof_every) == 0) slot = g_prof_calls++;
     prof_lock.unlock();
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), stream);
-    // head_dim 128 runs on the matrix cores with the LDS prefetch ring; head_dim 64 on the vector-ALU kernel
-    const int lrc = r.d == 128 ? kvp::launch_attn_mfma(r.p, r.elem, r.bs, stream)
-                               : kvp::launch_attn_valu(r.p, r.elem, r.d, r.bs, stream);
-    if (lrc == -2) return fail(KV_ERR_HIP, "kv_decode_attn: could not raise the dynamic LDS limit of the kernel");
-    if (lrc != 0)
+    if (kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, stream) != 0)
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);
-    if (r.d == 128) {
-        kvp::launch_finalize_mfma(r.p, r.elem, r.bs, stream);
-        if (int rc = check_launch("kv_decode_attn finalize kernel")) return rc;
-    } else if (r.split) {
-        kvp::launch_reduce(r.p, r.elem, r.d, r.bs, stream);
-        if (int rc = check_launch("kv_decode_attn combine kernel")) return rc;
-    }
+    kvp::launch_finalize_mfma(r.p, r.elem, r.d, r.bs, stream);
+    if (int rc = check_launch("kv_decode_attn merge kernel")) return rc;
     return KV_OK;
 }
 
@@ -282,7 +246,7 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
     qview.shape[0] = B; qview.shape[1] = Hq; qview.shape[2] = d;
     qview.stride[0] = gemm_out->stride[0]; qview.stride[1] = d; qview.stride[2] = 1;
 
-    const bool touch = cross_layer_prefetch != 0 && d == 128;
+    const bool touch = cross_layer_prefetch != 0;
     if (touch) {
         std::lock_guard<std::mutex> lock(g_side_mutex);
         if (!g_side_stream) {
@@ -301,7 +265,7 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
         if (touch) {        // fork: touch this layer's leading KV tiles while the dense layer runs
             (void)hipEventRecord(g_fork_event, main_stream);
             (void)hipStreamWaitEvent(g_side_stream, g_fork_event, 0);
-            kvp::launch_touch_mfma(r.p, r.bs, kTouchTiles, (uint32_t*)r.p.partials, g_side_stream);
+            kvp::launch_touch_mfma(r.p, r.d, r.bs, kTouchTiles, (uint32_t*)r.p.partials, g_side_stream);
             (void)hipEventRecord(g_join_event, g_side_stream);
         }
         const kv_tensor* wl = weights[l];
@@ -319,9 +283,8 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
 }
 
 size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size) {
-    if (B <= 0 || Hq <= 0 || d <= 0 || max_context <= 0 || block_size <= 0) return 0;
-    const int64_t mc = ((int64_t)max_context + block_size - 1) / block_size * block_size;
-    return workspace_bytes(B, Hq, d, mc, part_tokens());
+    if (B <= 0 || Hq <= 0 || (d != 64 && d != 128) || max_context <= 0 || block_size <= 0) return 0;
+    return workspace_bytes(Hq, d);
 }
 
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {
@@ -334,15 +297,6 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {
     return KV_OK;
 }
 
-int kv_decode_set_partition_tokens(int tokens) {
-    if (tokens != 0 && (tokens < 128 || tokens > 65536 || tokens % 128))
-        return fail(KV_ERR_INVALID, "kv_decode_set_partition_tokens: %d is not 0 or a multiple of 128 in 128..65536", tokens);
-    g_part_tokens.store(tokens);
-    return KV_OK;
-}
-
-int kv_decode_get_partition_tokens(void) { return part_tokens(); }
-
 int kv_decode_set_waves_per_cu(int waves) {
     if (waves < 0 || waves > kMaxWavesPerCU)
         return fail(KV_ERR_INVALID, "kv_decode_set_waves_per_cu: %d outside 0..%d", waves, kMaxWavesPerCU);
@@ -350,18 +304,21 @@ int kv_decode_set_waves_per_cu(int waves) {
     return KV_OK;
 }
 
-int kv_decode_get_waves_per_cu(int prefetch_distance) {
-    if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE) return 0;
-    return waves_per_cu(prefetch_distance);
+int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim) {
+    if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE || (head_dim != 64 && head_dim != 128)) return 0;
+    return waves_per_cu(prefetch_distance, head_dim);
 }
 
-int kv_profile_enable(int max_calls) {
+int kv_profile_enable(int max_calls, int every) {
     if (max_calls < 0 || max_calls > 100000) return fail(KV_ERR_INVALID, "kv_profile_enable: max_calls %d outside 0..100000", max_calls);
+    if (every < 1) return fail(KV_ERR_INVALID, "kv_profile_enable: every %d must be at least 1", every);
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     for (hipEvent_t ev : g_prof_events) (void)hipEventDestroy(ev);
     g_prof_events.clear();
     g_prof_capacity = 0;
     g_prof_calls = 0;
+    g_prof_seen = 0;
+    g_prof_every = every;
     for (int i = 0; i < 2 * max_calls; ++i) {
         hipEvent_t ev;
         hipError_t e = hipEventCreate(&ev);
@@ -389,6 +346,7 @@ int kv_profile_read(double* main_ms_sum, int* calls) {
         *main_ms_sum += a;
     }
     g_prof_calls = 0;
+    g_prof_seen = 0;
     return KV_OK;
 }
 

@@ -43,29 +43,22 @@ def test_closed_forms_match_the_paper_worked_example():
 
 
 def test_workspace_size_formula():
-    P = kv.kv_decode_get_partition_tokens()
-    # head_dim 64: one partial per (sequence, head, partition); nothing when one partition suffices
-    assert kv.kv_decode_workspace_bytes(8, 32, 64, P, 16) == 0
-    np_ = -(-32768 // P)
-    assert kv.kv_decode_workspace_bytes(8, 32, 64, 32768, 16) == 8 * 32 * np_ * 66 * 4
-    # head_dim 128: two partial pieces of min(Hq, 16) rows of 132 floats for each of at most 4096 workers
+    # two partial pieces of min(Hq, 16) rows of d + 4 floats for each of at most 4096 workers
     assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == 4096 * 2 * 16 * 132 * 4
     assert kv.kv_decode_workspace_bytes(1, 4, 128, 16, 16) == 4096 * 2 * 4 * 132 * 4
-    with pytest.raises(kv.KVError):
-        kv.kv_decode_set_partition_tokens(100)
-    kv.kv_decode_set_partition_tokens(1024)
-    assert kv.kv_decode_get_partition_tokens() == 1024
-    kv.kv_decode_set_partition_tokens(0)
-    assert kv.kv_decode_get_partition_tokens() == P
+    assert kv.kv_decode_workspace_bytes(2, 4, 64, 128, 16) == 4096 * 2 * 4 * 68 * 4
+    assert kv.kv_decode_workspace_bytes(2, 4, 96, 128, 16) == 0
 
 
 def test_waves_per_cu_follow_the_lds_budget():
-    # a worker's ring is (distance + 1) x 8 KB; 160 KB of LDS per compute unit; automatic choice is at most 6;
-    # odd counts above one are rounded down
-    assert [kv.kv_decode_get_waves_per_cu(d) for d in range(5)] == [6, 6, 6, 4, 4]
+    # a worker's ring is (distance + 1) x 8 KB at head_dim 128 (4 KB at 64); 160 KB of LDS per compute unit;
+    # the automatic choice is at most 6; odd counts above one are rounded down
+    assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [6, 6, 6, 4, 4]
+    assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [6, 6, 6, 6, 6]
     kv.kv_decode_set_waves_per_cu(16)
     try:
-        assert [kv.kv_decode_get_waves_per_cu(d) for d in range(5)] == [16, 10, 6, 4, 4]
+        assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [16, 10, 6, 4, 4]
+        assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [16, 16, 12, 10, 8]
         with pytest.raises(kv.KVError):
             kv.kv_decode_set_waves_per_cu(17)
     finally:
@@ -126,13 +119,10 @@ def test_scalar_arguments_are_checked():
     assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], bs=8) == 2
 
 
-def test_missing_workspace_is_reported():
+def test_workspace_registration_arguments_are_checked():
     lib = kv.load_library()
     assert lib.kv_decode_set_workspace(None, 0) == 0
-    binding._registered = (0, 0)
-    f = torch.bfloat16                                # head_dim 64 with 65536 tokens: needs split-KV scratch
-    a = dict(q=_fake((3, 8, 64), f), k=_fake((10, 2, 16, 64), f), v=_fake((10, 2, 16, 64), f),
-             bt=_fake((3, 4096), torch.int32), cl=_fake((3,), torch.int32), out=_fake((3, 8, 64), f))
-    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"]) == 4
-    assert "workspace" in kv.kv_last_error()
     assert lib.kv_decode_set_workspace(ctypes.c_void_p(0x1000), 0) == 1
+    assert lib.kv_decode_set_workspace(None, 64) == 1
+    assert lib.kv_decode_set_workspace(ctypes.c_void_p(0x1004), 64) == 1
+    binding._registered = (0, 0)

@@ -50,40 +50,44 @@ def test_every_prefetch_distance_gives_the_same_result(pd):
     assert torch.equal(got, ref), "prefetching must not change any value"
 
 
-def test_split_kv_partitions_and_combine():
-    """Contexts spanning many partitions, including lengths at partition boundaries."""
-    P = kv.kv_decode_get_partition_tokens()
-    lens = [P - 1, P, P + 1, 3 * P + 17, 8 * P, 1, 0, 5 * P - 16]
-    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 11, DEV, poison=True, lens=lens)
-    got = run_hip(c, 1)
-    want = run_oracle(c)
-    compare(got, want, "split")
-    assert (got[6] == 0).all()          # empty context -> zero row
+def test_missing_workspace_is_reported():
+    """Every call needs the registered split-KV scratch; without it the call fails before any launch."""
+    from paper_2504_06319_amd import binding
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 3, DEV, lens=[50, 70])
+    lib = kv.load_library()
+    assert lib.kv_decode_set_workspace(None, 0) == 0
+    binding._registered = (0, 0)
+    descs = [binding.describe(t) for t in (c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"],
+                                           torch.empty_like(c["q"]))]
+    import ctypes
+    rc = lib.kv_decode_attn(*[ctypes.byref(d) for d in descs], c["scale"], 2, 16, 1, None)
+    assert rc == 4 and "workspace" in kv.kv_last_error()
+    check_case(c, 1, "after re-registration")          # the binding registers its buffer again
 
 
-@pytest.mark.parametrize("P", [128, 256, 2048])
-def test_other_partition_sizes(P):
-    """head_dim 64 path: partition size of the split-KV grid."""
-    kv.kv_decode_set_partition_tokens(P)
-    try:
-        c = synth.make_case(_cfg(4, 1, 64, 32, "bf16"), 13, DEV, poison=True, lens=[P + 5, 4 * P, 77, 6 * P + 1])
-        check_case(c, 2, f"P={P}")
-    finally:
-        kv.kv_decode_set_partition_tokens(0)
+def test_lengths_around_worker_range_boundaries():
+    """Contexts whose tile counts straddle the equal shares of the flat tile space, an empty one included."""
+    lens = [511, 512, 513, 3 * 512 + 17, 8 * 512, 1, 0, 5 * 512 - 16]
+    for d in (128, 64):
+        c = synth.make_case(_cfg(8, 2, d, 16, "bf16"), 11, DEV, poison=True, lens=lens)
+        got = run_hip(c, 1)
+        compare(got, run_oracle(c), f"d={d}")
+        assert (got[6] == 0).all()          # empty context -> zero row
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("waves", [1, 3, 8, 16])
 @pytest.mark.parametrize("pd", [0, 1, 4])
-def test_other_worker_counts_cut_units_differently(waves, pd):
-    """head_dim 128 path: the number of persistent workers decides where units are cut into pieces;
+def test_other_worker_counts_cut_units_differently(waves, pd, d):
+    """The number of persistent workers decides where units are cut into pieces;
     every cut must give the same result.  One long sequence spans hundreds of workers, short
     ones are covered whole, empty ones get zero rows."""
     kv.kv_decode_set_waves_per_cu(waves)
     try:
         lens = [40000, 0, 5, 16, 17, 3000, 0, 1, 12345, 640, 0]
-        c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 43 + waves, DEV, poison=True, lens=lens)
+        c = synth.make_case(_cfg(8, 2, d, 16, "bf16"), 43 + waves, DEV, poison=True, lens=lens)
         got = run_hip(c, pd)
-        compare(got, run_oracle(c), f"waves={waves} pd={pd}")
+        compare(got, run_oracle(c), f"waves={waves} pd={pd} d={d}")
         for b, n in enumerate(lens):
             if n == 0:
                 assert (got[b] == 0).all()
