@@ -41,7 +41,7 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     main_ms, n = kv.kv_profile_read()
-    kv.kv_profile_enable(0)
+    kv.kv_profile_enable(0, 1)
     assert n == (steps + every - 1) // every
     return (t1 - t0) * 1e3 / steps, main_ms / n
 
@@ -76,6 +76,49 @@ def layer_stack(kv, torch, synth, dev, steps, warmup, pd, cross, layers=None):
     kvb = synth.kv_bytes(lens, cfg["Hkv"], cfg["d"]) * L
     wb = cfg["gemm_k"] * cfg["gemm_n"] * 2 * L
     return ms, kvb, wb, cfg, L
+
+
+HEATMAP_MODELS = {               # attention shapes of the paper's four models (Section 4.1), head_dim 128, 16-token blocks
+    "mha_32q_32kv": (32, 32), "gqa_32q_8kv": (32, 8), "gqa_28q_4kv": (28, 4), "gqa_40q_8kv": (40, 8),
+}
+
+
+def heatmap(kv, torch, synth, dev, pd_on, steps=20, warmup=4):
+    """Synthetic counterpart of the paper's batch x sequence-length sweep (Section 4.3, Figure 4): main-kernel time
+    with the look-ahead on and off for every (model shape, batch, context) cell; equal context lengths per cell."""
+    rows = []
+    for name, (Hq, Hkv) in HEATMAP_MODELS.items():
+        for B in (1, 4, 16, 64, 128):
+            for ctx in (1024, 2560, 4608, 8704):             # 512 input tokens + 512 .. 8192 generated
+                cfg = dict(Hq=Hq, Hkv=Hkv, d=128, bs=16, dtype="bf16")
+                cases = []
+                for i in range(2):
+                    c = synth.make_case(cfg, synth.BASE_SEED + 17 * i, dev, lens=[ctx] * B)
+                    c["out"] = torch.empty_like(c["q"])
+                    cases.append(c)
+                kvb = synth.kv_bytes([ctx] * B, Hkv, 128)
+                t = {}
+                for label, pd in (("on", pd_on), ("off", 0)):
+                    def step(i):
+                        c = cases[i % 2]
+                        kv.kv_decode_attn(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"],
+                                          c["out"], c["scale"], Hkv, 16, pd)
+                    for i in range(warmup):
+                        step(i)
+                    kv.kv_profile_enable(steps, 1)
+                    torch.cuda.synchronize()
+                    for i in range(steps):
+                        step(i)
+                    torch.cuda.synchronize()
+                    ms, n = kv.kv_profile_read()
+                    kv.kv_profile_enable(0, 1)
+                    t[label] = ms / n
+                rows.append({"model": name, "batch": B, "context": ctx, "kv_bytes": kvb, "on_us": t["on"] * 1e3,
+                             "off_us": t["off"] * 1e3, "speedup": t["off"] / t["on"], "on_GBps": kvb / t["on"] / 1e6})
+                del cases
+                torch.cuda.empty_cache()
+        log(f"[bench] heat-map {name} done")
+    return rows
 
 
 def cpu_baseline(oracle, synth, case, cfg, budget_s=20.0):
@@ -118,6 +161,8 @@ def main():
     ap.add_argument("--layer-stack-only", type=int, default=0, metavar="LAYERS",
                     help="run only the layer stack with this many layers and print its record (profiling aid)")
     ap.add_argument("--cross-layer-touch", type=int, default=0)
+    ap.add_argument("--heatmap", action="store_true",
+                    help="print the on/off sweep over model shape x batch x context length and exit")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run plain 1 GiB device copies, so a counter run sees a copy kernel of known traffic")
     args = ap.parse_args()
@@ -166,6 +211,10 @@ def main():
         torch.cuda.empty_cache()
 
     pd_on = args.prefetch_distance if args.prefetch_distance is not None else 2
+    if args.heatmap:
+        print(json.dumps({"heatmap": heatmap(kv, torch, synth, dev, pd_on), "prefetch_distance": pd_on,
+                          "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, 128)}), flush=True)
+        return
     if args.layer_stack_only:
         lms, lkvb, lwb, lcfg, L = layer_stack(kv, torch, synth, dev, args.steps, args.warmup, pd_on, args.cross_layer_touch,
                                               layers=args.layer_stack_only)
