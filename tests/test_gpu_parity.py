@@ -107,6 +107,42 @@ def test_more_sequences_than_lanes_in_the_length_scan():
     check_case(c, 1, "300 sequences")
 
 
+@pytest.mark.parametrize("G,d", [(16, 128), (12, 128), (16, 64), (3, 64)])
+def test_wide_query_groups(G, d):
+    """Up to 16 query heads per kv head fill every row of the 16-wide MFMA tile."""
+    c = synth.make_case(_cfg(G, 1, d, 16, "bf16"), 200 + G, DEV, poison=True, lens=[1, 17, 400, 2500])
+    check_case(c, 2, f"G={G} d={d}")
+
+
+def test_lengths_beyond_the_table_are_clamped_to_it():
+    """context_lens larger than MB * block_size attend over the MB * block_size tokens the table can name."""
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 59, DEV, lens=[160, 320, 48])       # table width 20 blocks
+    want = run_oracle(c)
+    c2 = dict(c)
+    c2["block_tables"] = c["block_tables"][:, :10].contiguous()                           # now 160 tokens at most
+    c2["context_lens"] = torch.tensor([160, 10 ** 9, 48], dtype=torch.int32, device=DEV)
+    got = run_hip(c2, 1)
+    c3 = dict(c, context_lens=torch.tensor([160, 160, 48], dtype=torch.int32, device=DEV))
+    want3 = run_oracle(c3)
+    compare(got, want3, "clamped")
+    compare(got[[0, 2]], want[[0, 2]], "untouched rows")
+
+
+def test_profile_events_sample_every_nth_call():
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 61, DEV, lens=[600, 900])
+    out = torch.empty_like(c["q"])
+    kv.kv_profile_enable(3, 2)
+    try:
+        for _ in range(5):
+            run_hip(c, 1, out=out)
+        ms, n = kv.kv_profile_read()
+        assert n == 3 and 0 < ms / n < 5.0
+        ms, n = kv.kv_profile_read()
+        assert n == 0
+    finally:
+        kv.kv_profile_enable(0, 1)
+
+
 def test_empty_and_single_token_contexts():
     c = synth.make_case(_cfg(4, 4, 64, 16, "f16"), 17, DEV, poison=True, lens=[0, 1, 0, 2])
     got = run_hip(c, 1)
