@@ -217,6 +217,24 @@ def test_large_logits_do_not_overflow():
     check_case(c, 1, "large logits")
 
 
+def test_one_million_token_context():
+    """A single unit of 65 537 tiles: every worker holds one piece of it and the merge kernel sees 1 536 pieces."""
+    n = (1 << 20) + 7
+    c = synth.make_case(_cfg(4, 1, 128, 16, "bf16"), 71, DEV, lens=[n])
+    got = run_hip(c, 2)
+    pairs = np.array([(0, 0), (0, 3)], np.int32)
+    compare(got[0, [0, 3]], run_oracle(c, pairs), "1M tokens")
+    assert torch.isfinite(got.float()).all()
+
+
+def test_four_thousand_short_sequences():
+    """A batch far wider than a wave: the length scan runs over 64 chunks and most units are a single tile."""
+    rng = np.random.default_rng(9)
+    lens = rng.integers(0, 40, 4096).tolist()
+    c = synth.make_case(_cfg(4, 2, 64, 16, "f16"), 73, DEV, poison=True, lens=lens)
+    check_case(c, 1, "4096 sequences")
+
+
 # ---------------------------------------------------------------- benchmark configurations at full size
 @pytest.mark.parametrize("index", [1, 2, 3])
 def test_full_size_configuration_on_sampled_rows(index):
