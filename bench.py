@@ -264,10 +264,12 @@ def main():
                                   "ms_per_step": ms0, "value": kvb / (ms0 * 1e-3) / 1e9,
                                   "kernel_ms": main0, "speedup_on_vs_off": ms0 / ms}
         log(f"[bench] off: {ms0:.4f} ms/step")
-        # the same comparison with few waves per compute unit, where occupancy cannot hide the HBM latency
-        # (the regime of the paper's baseline kernel, Table 1)
+        # The two legs above each run at the occupancy the library picks for them (few waves with look-ahead,
+        # many without).  The same comparison at EQUAL occupancy: with two waves per compute unit occupancy
+        # cannot hide the HBM latency (the regime of the paper's baseline kernel, Table 1) and the look-ahead
+        # does; with four or six it can, and the look-ahead adds nothing.
         low = {}
-        for wpc in (2, 4):
+        for wpc in (2, 4, 6):
             kv.kv_decode_set_waves_per_cu(wpc)
             _, _, _, l_on, lk_on = measure(args.workload, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
             _, _, _, l_off, lk_off = measure(args.workload, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
@@ -275,7 +277,7 @@ def main():
                                          "off_kernel_ms": lk_off, "kernel_speedup_on_vs_off": lk_off / lk_on}
             log(f"[bench] waves/CU {wpc}: on {lk_on:.4f} ms, off {lk_off:.4f} ms kernel")
         kv.kv_decode_set_waves_per_cu(args.waves_per_cu)
-        result["prefetch_on_vs_off_low_occupancy"] = low
+        result["prefetch_on_vs_off_equal_occupancy"] = low
         others = {}
         for idx in (1, 2, 3):
             if idx == args.workload:

@@ -116,7 +116,9 @@ size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int bloc
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
 
 /*
- * Persistent waves (workers) per compute unit, 1 .. 16; 0 restores the automatic choice (6).
+ * Persistent waves (workers) per compute unit, 1 .. 16; 0 restores the automatic choice, which
+ * aims at 32-48 KB of KV in flight per compute unit: 6 waves at prefetch distance 0 or 1 and 2
+ * waves at distance 2 or more for head_dim 128, 8 and 4 waves for head_dim 64.
  * Each worker holds (prefetch_distance + 1) stages of LDS (8 KB each at head_dim 128, 4 KB at
  * 64), so the number in effect is capped by the 160 KB of a compute unit (Eq. 2 re-derived
  * for LDS as the prefetch target: bytes in flight per CU = stage x prefetch_distance x waves);

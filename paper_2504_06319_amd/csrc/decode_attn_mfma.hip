@@ -69,9 +69,48 @@ __device__ __forceinline__ float4v mfma_k16(u32x2 a, u32x2 b, float4v c) {
         return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, a), __builtin_bit_cast(half4, b), c, 0, 0, 0);
 }
 
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+// Two floats -> two 16-bit patterns in one dword (lo in bits 15:0), round to nearest even; one packed convert.
 template <Elem E>
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    return (uint32_t)pack1<E>(lo) | ((uint32_t)pack1<E>(hi) << 16);
+    const float2v f = {lo, hi};
+    if constexpr (E == Elem::BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, half2v));
+}
+
+// The values of the lanes 16 and 32 away (lane ^ 16, lane ^ 32), by the lane-swap instructions: a register-file
+// operation, where a shuffle would be a round trip through the LDS crossbar on the critical path of every tile.
+// v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of its second,
+// v_permlane32_swap the upper half of the first with the lower half of the second; fed the same value twice, the
+// two results hold, for every lane, its own value and the partner's, in some order.
+struct LanePair { float a, b; };
+__device__ __forceinline__ LanePair swap16(float v) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, v);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const uint32_t r0 = r[0], r1 = r[1];        // copies: a bit_cast applied to a vector element reads element 0
+    return {__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+__device__ __forceinline__ LanePair swap32(float v) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const uint32_t r0 = r[0], r1 = r[1];        // copies: a bit_cast applied to a vector element reads element 0
+    return {__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+// max / sum over the four lanes {lr, lr + 16, lr + 32, lr + 48}
+__device__ __forceinline__ float group_max(float v) {
+    LanePair p = swap16(v);
+    v = fmaxf(p.a, p.b);
+    p = swap32(v);
+    return fmaxf(p.a, p.b);
+}
+__device__ __forceinline__ float group_sum(float v) {
+    LanePair p = swap16(v);
+    v = p.a + p.b;
+    p = swap32(v);
+    return p.a + p.b;
 }
 
 template <int N>
@@ -179,7 +218,7 @@ __device__ __forceinline__ int scan_total(const_i32_ptr cl, int B, int max_len, 
         const int t = idx < B ? tiles_of(clamp_len(cl[idx], max_len)) : 0;
         total += wave_sum_i32(t);
     }
-    return total;
+    return __builtin_amdgcn_readfirstlane(total);   // every lane holds the sum: make it a scalar for the compiler too
 }
 
 __device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len, int lane, int Hkv,
@@ -304,7 +343,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
 
     auto issue = [&](const Cursor& c, int stage) {   // asynchronous fetch of one K tile and one V tile into a stage
         int phys = bt[(int64_t)c.b * p.bt_stride_b + c.j / TPB];   // only entries of tiles inside the range are read
-        phys = min(max(phys, 0), p.NBLK - 1);
+        phys = __builtin_amdgcn_readfirstlane(min(max(phys, 0), p.NBLK - 1));
         const int sub = (c.j % TPB) * kTileBytes;
         const unsigned char* kt = kcache + ((int64_t)phys * p.kv_stride_blk + (int64_t)c.kvh * p.kv_stride_h) * 2 + sub;
         const unsigned char* vt_ = vcache + ((int64_t)phys * p.v_stride_blk + (int64_t)c.kvh * p.v_stride_h) * 2 + sub;
@@ -371,9 +410,15 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         // ---- S^T = K Q^T once the K operands are back (the CB reads of V may still be outstanding)
         if constexpr (KJ == 4) lds_wait_k<CB>(ka[0], ka[1], ka[2], ka[3]);
         else lds_wait_k<CB>(ka[0], ka[1]);
-        float4v sacc = {0.f, 0.f, 0.f, 0.f};
+        // two independent accumulation chains: a dependent MFMA waits for the previous one's full latency
+        float4v sacc = mfma_k32<E>(ka[0], qb[0], float4v{0.f, 0.f, 0.f, 0.f});
+        float4v sacc1 = mfma_k32<E>(ka[1], qb[1], float4v{0.f, 0.f, 0.f, 0.f});
 #pragma unroll
-        for (int j = 0; j < KJ; ++j) sacc = mfma_k32<E>(ka[j], qb[j], sacc);
+        for (int j = 2; j < KJ; j += 2) {
+            sacc = mfma_k32<E>(ka[j], qb[j], sacc);
+            sacc1 = mfma_k32<E>(ka[j + 1], qb[j + 1], sacc1);
+        }
+        sacc += sacc1;
         lds_wait_v(va);
 
         // ---- online softmax over this tile's 16 tokens (lane holds tokens 4 lq + i of head lr)
@@ -392,9 +437,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) { va[cb][0] &= m01; va[cb][1] &= m23; }
         }
-        float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mx = group_max(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])));
         const float m_new = fmaxf(m, mx);
         if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {      // some head's maximum moved: rescale
             const float alpha = fast_exp2(m - m_new);
@@ -419,8 +462,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         const bool unit_end = ca.j + 1 == ca.ntiles;
         const bool range_end = r + 1 == r1;
         if (unit_end || range_end) {
-            float lt = l + __shfl_xor(l, 16);
-            lt += __shfl_xor(lt, 32);
+            const float lt = group_sum(l);
             if (lr < G) {
                 if (piece_first_j == 0 && unit_end) {           // the whole unit was ours: final rows
                     const float inv = 1.0f / lt;                // lt > 0: a unit has at least one valid token

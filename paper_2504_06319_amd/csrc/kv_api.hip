@@ -41,16 +41,21 @@ int num_cus() {
     return n;
 }
 
-// Persistent waves per compute unit of the attention kernel: what the caller asked for, else 6 (measured
-// best: about 48-96 KB of KV in flight per compute unit), capped by the LDS the rings need.  Odd counts above
-// one are rounded down: 5 and 10 waves per compute unit measured about 25 % slower than 4 and 8.
+// Persistent waves per compute unit of the attention kernel: what the caller asked for, else a count chosen
+// for the bytes it puts in flight.  The kernel runs fastest with about 32-48 KB of KV requested per compute
+// unit at any time; beyond that throughput falls again (measured: 64-96 KB in flight costs 4-8 %).  A wave
+// keeps max(1, distance) tile pairs of 8 KB (head_dim 128) or 4 KB (head_dim 64) in flight, so deep look-ahead
+// wants few waves and no look-ahead wants many; head_dim 64 needs at least four waves to keep up with the
+// arithmetic of its smaller tiles.  Always capped by the LDS the rings need.
 int waves_per_cu(int prefetch_distance, int d) {
     const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance, d);
     int w = g_waves_per_cu.load();
-    if (w <= 0) w = 6;
+    if (w <= 0) {
+        if (d == 128) w = prefetch_distance <= 1 ? 6 : 2;
+        else w = prefetch_distance <= 1 ? 8 : 4;
+    }
     w = w < lds_limit ? w : lds_limit;
     w = w < kMaxWavesPerCU ? w : kMaxWavesPerCU;
-    if (w > 2 && (w & 1)) --w;
     return w;
 }
 

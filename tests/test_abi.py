@@ -51,14 +51,16 @@ def test_workspace_size_formula():
 
 
 def test_waves_per_cu_follow_the_lds_budget():
-    # a worker's ring is (distance + 1) x 8 KB at head_dim 128 (4 KB at 64); 160 KB of LDS per compute unit;
-    # the automatic choice is at most 6; odd counts above one are rounded down
-    assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [6, 6, 6, 4, 4]
-    assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [6, 6, 6, 6, 6]
+    # automatic choice: many waves with little or no look-ahead, few with deep look-ahead (32-48 KB of KV in
+    # flight per compute unit), never fewer than four at head_dim 64
+    assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [6, 6, 2, 2, 2]
+    assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [8, 8, 4, 4, 4]
+    # an explicit request is capped by LDS: a worker's ring is (distance + 1) x 8 KB at head_dim 128 (4 KB at
+    # 64), a compute unit has 160 KB
     kv.kv_decode_set_waves_per_cu(16)
     try:
-        assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [16, 10, 6, 4, 4]
-        assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [16, 16, 12, 10, 8]
+        assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [16, 10, 6, 5, 4]
+        assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [16, 16, 13, 10, 8]
         with pytest.raises(kv.KVError):
             kv.kv_decode_set_waves_per_cu(17)
     finally:
