@@ -86,8 +86,13 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
  * (next iteration, Section 3.1); the cross-layer form is this repository's harness.
  *
  *   x        [B, K] bf16, rows dense;  gemm_out [B, N] bf16, rows dense, N >= Hq*d when q == NULL
- *   weights[l] bf16, either [K, N] row-major or tile-packed [N/128, K, 128] (column tile t holds
- *            W[:, 128t : 128t+128] as one contiguous K x 128 run: the form the kernel streams fastest)
+ *   weights[l] bf16, one of
+ *            [K, N] row-major;
+ *            [N/128, K, 128] tile-packed (column tile t holds W[:, 128t : 128t+128] as one contiguous run);
+ *            [N/64, K/32, 4, 64, 8] in matrix-core operand order,
+ *                Wp[t][ks][nb][l][j] = W[32 ks + 8 (l / 16) + j][64 t + 16 nb + l % 16],
+ *            the form the kernel streams fastest (HBM straight into registers); it needs K of 1024, 2048,
+ *            4096 or 8192 and a workspace of kv_layerstack_workspace_bytes()
  *   q, k_caches, v_caches, outs: arrays of num_layers tensor pointers (host arrays of
  *   host structs naming device memory).  Supported GEMM shapes: B <= 128, K % 128 == 0,
  *   N % 128 == 0.
@@ -102,11 +107,16 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
 /*
  * Split-KV workspace (the block index range [s, e) that Algorithm 1 takes as input lets a
  * worker own part of a sequence; the pieces of a sequence that several workers share are
- * merged by a second kernel).  Bytes a call with these extents needs: a fixed bound, two
- * partial pieces of min(Hq, 16) rows of (d + 4) floats for each of at most 4096 workers
- * (69 MB at d 128, Hq >= 16).  0 for unsupported extents.
+ * merged by a second kernel).  Bytes a call with these extents needs: a fixed bound, 4096 bytes
+ * of words the dense layer of the layer stack uses, then two partial pieces of min(Hq, 16) rows
+ * of (d + 4) floats for each of at most 4096 workers (69 MB at d 128, Hq >= 16).  0 for
+ * unsupported extents.
+ * kv_layerstack_workspace_bytes: what kv_decode_layerstack needs when weights are in operand
+ * order: the same plus two fp32 partial tiles of 128 x 128 per 128 columns of the dense layer
+ * (its two halves of K meet there); gemm_n = columns of the dense layer.
  */
 size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size);
+size_t kv_layerstack_workspace_bytes(int num_q_heads, int head_dim, int gemm_n);
 
 /*
  * Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters.

@@ -38,7 +38,8 @@ class KVTensor(ctypes.Structure):
 
 
 EXPORTS = [
-    "kv_decode_attn", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_decode_set_workspace",
+    "kv_decode_attn", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
+    "kv_decode_set_workspace",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_profile_enable", "kv_profile_read",
 ]
@@ -68,6 +69,8 @@ def load_library():
                                                  ctypes.c_void_p]
             lib.kv_decode_workspace_bytes.restype = ctypes.c_size_t
             lib.kv_decode_workspace_bytes.argtypes = [ctypes.c_int] * 5
+            lib.kv_layerstack_workspace_bytes.restype = ctypes.c_size_t
+            lib.kv_layerstack_workspace_bytes.argtypes = [ctypes.c_int] * 3
             lib.kv_decode_set_workspace.restype = ctypes.c_int
             lib.kv_decode_set_workspace.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
             lib.kv_decode_set_waves_per_cu.restype = ctypes.c_int
@@ -145,6 +148,10 @@ def kv_decode_workspace_bytes(B: int, Hq: int, d: int, max_context: int, block_s
     return int(load_library().kv_decode_workspace_bytes(B, Hq, d, max_context, block_size))
 
 
+def kv_layerstack_workspace_bytes(Hq: int, d: int, gemm_n: int) -> int:
+    return int(load_library().kv_layerstack_workspace_bytes(Hq, d, gemm_n))
+
+
 def kv_decode_set_waves_per_cu(waves: int):
     _check(load_library().kv_decode_set_waves_per_cu(int(waves)))
 
@@ -182,6 +189,8 @@ def kv_decode_layerstack(x, weights, gemm_out, q, k_caches, v_caches, block_tabl
     o0 = outs[0]
     need = kv_decode_workspace_bytes(o0.shape[0], o0.shape[1], o0.shape[2],
                                      block_tables.shape[1] * block_size, block_size)
+    if any(w.dim() == 5 for w in weights):
+        need = max(need, kv_layerstack_workspace_bytes(o0.shape[1], o0.shape[2], gemm_out.shape[1]))
     _ensure_workspace(x.device, need)
     w_arr, w_keep = _desc_array(weights)
     k_arr, k_keep = _desc_array(k_caches)
@@ -210,12 +219,26 @@ def kv_profile_read():
     return a.value, n.value
 
 
-def pack_weights(w: torch.Tensor) -> torch.Tensor:
-    """Re-lay a [K, N] weight matrix as [N/128, K, 128] (one contiguous run per 128-column tile); set-up time."""
+def pack_weights(w: torch.Tensor, layout: str = "operand") -> torch.Tensor:
+    """Re-lay a [K, N] weight matrix for the dense layer; set-up time, pure data movement.
+
+    ``"operand"``: [N/64, K/32, 4, 64, 8], the order in which the matrix cores read the B operand,
+    ``Wp[t, ks, nb, l, j] = W[32 ks + 8 (l // 16) + j, 64 t + 16 nb + l % 16]`` (K must be 1024, 2048, 4096 or
+    8192): the fast path, weights go from HBM straight into registers.
+    ``"tile"``: [N/128, K, 128], one contiguous run per 128-column tile, for the kernel that stages W through LDS.
+    """
     K, N = w.shape
-    if N % 128:
-        raise KVError(1, "pack_weights: N must be a multiple of 128")
-    return w.reshape(K, N // 128, 128).permute(1, 0, 2).contiguous()
+    if layout == "tile":
+        if N % 128:
+            raise KVError(1, "pack_weights: N must be a multiple of 128")
+        return w.reshape(K, N // 128, 128).permute(1, 0, 2).contiguous()
+    if layout != "operand":
+        raise KVError(1, f"pack_weights: unknown layout {layout!r}")
+    if N % 64 or K % 32:
+        raise KVError(1, "pack_weights: N must be a multiple of 64 and K of 32")
+    # W[ks, lq, j, t, nb, lr] -> Wp[t, ks, nb, (lq, lr), j]
+    return (w.reshape(K // 32, 4, 8, N // 64, 4, 16).permute(3, 0, 4, 1, 5, 2).contiguous()
+            .reshape(N // 64, K // 32, 4, 64, 8))
 
 
 def kv_block_bytes(elem_bytes: int, head_dim: int, block_size: int) -> int:

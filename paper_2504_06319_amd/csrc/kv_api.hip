@@ -59,9 +59,14 @@ int waves_per_cu(int prefetch_distance, int d) {
     return w;
 }
 
-// Two partial pieces of G rows per worker, sized for the largest launch.
-size_t workspace_bytes(int Hq, int d) {
+// Workspace layout: the dense layer's ticket words, the attention partials (two pieces of G rows per worker,
+// sized for the largest launch), then the dense layer's partial tiles (layer stack with weights in operand
+// order only).
+size_t attn_partial_region(int Hq, int d) {
     return kvp::mfma_partial_bytes(kvp::kMaxMfmaWorkers, Hq < 16 ? Hq : 16, d);
+}
+size_t workspace_bytes(int Hq, int d) {
+    return kvp::kGemmTicketBytes + attn_partial_region(Hq, d);
 }
 
 bool dense_tile(const kv_tensor* t) {   // [NBLK, Hkv, bs, d] with the [bs, d] tile contiguous
@@ -149,11 +154,11 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
     const int nw = cus * waves_per_cu(prefetch_distance, (int)d);
     p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
-    const size_t need = kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
+    const size_t need = kvp::kGemmTicketBytes + kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     if (!g_ws_ptr || g_ws_bytes < need)
         return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
-    p.partials = (float*)g_ws_ptr;
+    p.partials = (float*)((unsigned char*)g_ws_ptr + kvp::kGemmTicketBytes);
     return KV_OK;
 }
 
@@ -232,9 +237,17 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
         const bool row_major = w->ndim == 2 && w->shape[0] == K && w->shape[1] == N && w->stride[1] == 1 && w->stride[0] % 8 == 0;
         const bool packed = w->ndim == 3 && w->shape[0] * 128 == N && w->shape[1] == K && w->shape[2] == 128 &&
                             w->stride[2] == 1 && w->stride[1] % 8 == 0 && w->stride[0] % 8 == 0;
-        if (w->dtype != KV_BF16 || ((uintptr_t)w->data) % 16 || !(row_major || packed))
-            return fail(KV_ERR_INVALID, "kv_decode_layerstack: weights[%d] must be bf16 [%lld, %lld] row-major or [%lld, %lld, 128] tile-packed",
-                        l, (long long)K, (long long)N, (long long)(N / 128), (long long)K);
+        // operand order [N/64][K/32][4][64][8], contiguous
+        const bool operand = w->ndim == 5 && w->shape[0] * 64 == N && w->shape[1] * 32 == K && w->shape[2] == 4 &&
+                             w->shape[3] == 64 && w->shape[4] == 8 && w->stride[4] == 1 && w->stride[3] == 8 &&
+                             w->stride[2] == 512 && w->stride[1] == 2048 && w->stride[0] == 2048 * w->shape[1];
+        if (w->dtype != KV_BF16 || ((uintptr_t)w->data) % 16 || !(row_major || packed || operand))
+            return fail(KV_ERR_INVALID, "kv_decode_layerstack: weights[%d] must be bf16 [%lld, %lld] row-major, [%lld, %lld, 128] tile-packed "
+                        "or [%lld, %lld, 4, 64, 8] in operand order",
+                        l, (long long)K, (long long)N, (long long)(N / 128), (long long)K, (long long)(N / 64), (long long)(K / 32));
+        if (operand && K != 1024 && K != 2048 && K != 4096 && K != 8192)
+            return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: weights in operand order need K of 1024, 2048, 4096 or 8192, not %lld",
+                        (long long)K);
         if (outs[l]->ndim != 3) return fail(KV_ERR_INVALID, "kv_decode_layerstack: outs[%d] must have rank 3", l);
     }
     const int64_t B = outs[0]->shape[0], Hq = outs[0]->shape[1], d = outs[0]->shape[2];
@@ -244,6 +257,25 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: GEMM shape [%lld x %lld] . [%lld x %lld] not covered (rows <= 128, K %% 128 == 0, N %% 128 == 0)",
                     (long long)M, (long long)K, (long long)K, (long long)N);
     hipStream_t main_stream = (hipStream_t)stream;
+
+    // weights in operand order: the dense layer splits K over two workgroups per column tile, which meet through
+    // ticket words at the head of the workspace and partial tiles behind the attention's region
+    bool any_operand = false;
+    for (int l = 0; l < num_layers; ++l) any_operand = any_operand || weights[l]->ndim == 5;
+    int* gemm_tickets = nullptr;
+    float* gemm_partials = nullptr;
+    if (any_operand) {
+        const size_t attn_region = attn_partial_region((int)Hq, (int)d);
+        const size_t need = kvp::kGemmTicketBytes + attn_region + kvp::layer_gemm_packed_partial_bytes((int)N);
+        std::lock_guard<std::mutex> lock(g_ws_mutex);
+        if (!g_ws_ptr || g_ws_bytes < need)
+            return fail(KV_ERR_WORKSPACE, "kv_decode_layerstack: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
+        gemm_tickets = (int*)g_ws_ptr;
+        gemm_partials = (float*)((unsigned char*)g_ws_ptr + kvp::kGemmTicketBytes + attn_region);
+        // the ticket words must be zero when the first dense layer starts (every launch leaves them zero again);
+        // a fill kernel rather than a memset, so that the call can be captured into a graph
+        kvp::launch_zero_words(gemm_tickets, (int)(kvp::kGemmTicketBytes / sizeof(int)), main_stream);
+    }
 
     // queries of layer l: the caller's tensor, or the leading Hq*d columns of the GEMM output viewed [B, Hq, d]
     kv_tensor qview;
@@ -274,10 +306,16 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
             (void)hipEventRecord(g_join_event, g_side_stream);
         }
         const kv_tensor* wl = weights[l];
-        const int64_t ldw = wl->ndim == 2 ? wl->stride[0] : wl->stride[1];
-        const int64_t w_tile_stride = wl->ndim == 2 ? 128 : wl->stride[0];
-        const int grc = kvp::launch_layer_gemm(x->data, wl->data, gemm_out->data, (int)M, (int)K, (int)N, x->stride[0], ldw,
-                                               w_tile_stride, gemm_out->stride[0], main_stream);
+        int grc;
+        if (wl->ndim == 5) {
+            grc = kvp::launch_layer_gemm_packed(x->data, wl->data, gemm_out->data, (int)M, (int)K, (int)N, x->stride[0],
+                                                gemm_out->stride[0], gemm_tickets, gemm_partials, main_stream);
+        } else {
+            const int64_t ldw = wl->ndim == 2 ? wl->stride[0] : wl->stride[1];
+            const int64_t w_tile_stride = wl->ndim == 2 ? 128 : wl->stride[0];
+            grc = kvp::launch_layer_gemm(x->data, wl->data, gemm_out->data, (int)M, (int)K, (int)N, x->stride[0], ldw,
+                                         w_tile_stride, gemm_out->stride[0], main_stream);
+        }
         if (grc == -2) return fail(KV_ERR_HIP, "kv_decode_layerstack: could not raise the dynamic LDS limit of the GEMM kernel");
         if (grc != 0) return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: GEMM shape not covered");
         if (int rc = check_launch("kv_decode_layerstack GEMM kernel")) return rc;
@@ -290,6 +328,11 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
 size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int block_size) {
     if (B <= 0 || Hq <= 0 || (d != 64 && d != 128) || max_context <= 0 || block_size <= 0) return 0;
     return workspace_bytes(Hq, d);
+}
+
+size_t kv_layerstack_workspace_bytes(int Hq, int d, int gemm_n) {
+    if (Hq <= 0 || (d != 64 && d != 128) || gemm_n < 128 || gemm_n % 128) return 0;
+    return workspace_bytes(Hq, d) + kvp::layer_gemm_packed_partial_bytes(gemm_n);
 }
 
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {

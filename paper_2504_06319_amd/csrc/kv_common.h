@@ -51,6 +51,11 @@ int launch_finalize_mfma(const AttnParams& p, int elem, int d, int bs, hipStream
 int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* sink, hipStream_t stream);
 int launch_layer_gemm(const void* x, const void* w, void* y, int M, int K, int N, int64_t ldx, int64_t ldw,
                       int64_t w_tile_stride, int64_t ldy, hipStream_t stream);
+int launch_layer_gemm_packed(const void* x, const void* wp, void* y, int M, int K, int N, int64_t ldx, int64_t ldy,
+                             int* tickets, float* partials, hipStream_t stream);
+size_t layer_gemm_packed_partial_bytes(int N);
+void launch_zero_words(int* p, int n, hipStream_t stream);
+constexpr size_t kGemmTicketBytes = 4096;      // head of the workspace: one ticket word per 128-column tile of the dense layer
 int mfma_worker_lds_bytes(int prefetch_distance, int d);
 size_t mfma_partial_bytes(int num_workers, int G, int d);
 constexpr int kMaxMfmaWorkers = 4096;

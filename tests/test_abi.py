@@ -44,10 +44,14 @@ def test_closed_forms_match_the_paper_worked_example():
 
 def test_workspace_size_formula():
     # two partial pieces of min(Hq, 16) rows of d + 4 floats for each of at most 4096 workers
-    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == 4096 * 2 * 16 * 132 * 4
-    assert kv.kv_decode_workspace_bytes(1, 4, 128, 16, 16) == 4096 * 2 * 4 * 132 * 4
-    assert kv.kv_decode_workspace_bytes(2, 4, 64, 128, 16) == 4096 * 2 * 4 * 68 * 4
+    # 4096 bytes of dense-layer ticket words, then two pieces of min(Hq, 16) rows of d + 4 floats per worker
+    assert kv.kv_decode_workspace_bytes(8, 32, 128, 32768, 16) == 4096 + 4096 * 2 * 16 * 132 * 4
+    assert kv.kv_decode_workspace_bytes(1, 4, 128, 16, 16) == 4096 + 4096 * 2 * 4 * 132 * 4
+    assert kv.kv_decode_workspace_bytes(2, 4, 64, 128, 16) == 4096 + 4096 * 2 * 4 * 68 * 4
     assert kv.kv_decode_workspace_bytes(2, 4, 96, 128, 16) == 0
+    # the layer stack with weights in operand order adds two fp32 tiles of 128 x 128 per 128 columns
+    assert kv.kv_layerstack_workspace_bytes(32, 128, 14336) == kv.kv_decode_workspace_bytes(1, 32, 128, 16, 16) + 112 * 2 * 128 * 128 * 4
+    assert kv.kv_layerstack_workspace_bytes(32, 128, 100) == 0
 
 
 def test_waves_per_cu_follow_the_lds_budget():
@@ -128,3 +132,22 @@ def test_workspace_registration_arguments_are_checked():
     assert lib.kv_decode_set_workspace(None, 64) == 1
     assert lib.kv_decode_set_workspace(ctypes.c_void_p(0x1004), 64) == 1
     binding._registered = (0, 0)
+
+
+def test_operand_order_packing_places_every_element():
+    # Wp[t, ks, nb, l, j] = W[32 ks + 8 (l // 16) + j, 64 t + 16 nb + l % 16], checked element by element
+    import torch
+    K, N = 64, 128
+    w = torch.arange(K * N, dtype=torch.int32).reshape(K, N).to(torch.float32)
+    wp = kv.pack_weights(w, "operand")
+    assert tuple(wp.shape) == (N // 64, K // 32, 4, 64, 8) and wp.is_contiguous()
+    for t in range(N // 64):
+        for ks in range(K // 32):
+            for nb in range(4):
+                for l in range(64):
+                    for j in range(8):
+                        assert wp[t, ks, nb, l, j] == w[32 * ks + 8 * (l // 16) + j, 64 * t + 16 * nb + l % 16]
+    tile = kv.pack_weights(w, "tile")
+    assert tuple(tile.shape) == (1, K, 128) and torch.equal(tile[0], w)
+    with pytest.raises(kv.KVError):
+        kv.pack_weights(w, "columns")

@@ -26,10 +26,10 @@ def _stack(L, B, Hq, Hkv, d, bs, K, N, lens, seed, poison=True):
     return cfg, layers, x, ws, y, outs
 
 
-def _run(layers, x, ws, y, outs, q=None, pd=2, cross=0, packed=False):
+def _run(layers, x, ws, y, outs, q=None, pd=2, cross=0, layout=None):
     c0 = layers[0]
-    if packed:
-        ws = [kv.pack_weights(w) for w in ws]
+    if layout:
+        ws = [kv.pack_weights(w, layout) for w in ws]
     kv.kv_decode_layerstack(x, ws, y, q, [c["k_cache"] for c in layers], [c["v_cache"] for c in layers],
                             c0["block_tables"], c0["context_lens"], outs, c0["scale"], c0["num_kv_heads"],
                             c0["block_size"], pd, cross)
@@ -46,12 +46,12 @@ def _ulp_close_bf16(got_bits, want_bits):
 
 
 @pytest.mark.parametrize("B", [128, 5, 70])
-@pytest.mark.parametrize("cross,packed", [(0, False), (1, True)])
-def test_small_stack_matches_oracle(B, cross, packed):
-    L, Hq, Hkv, d, bs, K, N = 3, 8, 2, 128, 16, 256, 1280
+@pytest.mark.parametrize("cross,layout,K", [(0, None, 256), (1, "tile", 256), (0, "operand", 1024), (1, "operand", 2048)])
+def test_small_stack_matches_oracle(B, cross, layout, K):
+    L, Hq, Hkv, d, bs, N = 3, 8, 2, 128, 16, 1280
     lens = np.random.default_rng(B).integers(1, 700, B).tolist()
     cfg, layers, x, ws, y, outs = _stack(L, B, Hq, Hkv, d, bs, K, N, lens, 61)
-    _run(layers, x, ws, y, outs, cross=cross, packed=packed)
+    _run(layers, x, ws, y, outs, cross=cross, layout=layout)
     xb = oracle.bits_of(x)
     for l in range(L):
         c = layers[l]
@@ -82,12 +82,12 @@ def test_explicit_queries_bypass_the_gemm_output():
     assert _ulp_close_bf16(oracle.bits_of(y), oracle.layer_gemm_bf16(oracle.bits_of(x), oracle.bits_of(ws[-1])))
 
 
-@pytest.mark.parametrize("packed", [False, True])
-def test_gemm_alone_on_the_benchmark_shape(packed):
+@pytest.mark.parametrize("layout", [None, "tile", "operand"])
+def test_gemm_alone_on_the_benchmark_shape(layout):
     """The stand-in dense layer at its full shape [128 x 4096] . [4096 x 14336], sampled columns on the oracle."""
     B, K, N, Hq, Hkv, d, bs = 128, 4096, 14336, 32, 8, 128, 16
     cfg, layers, x, ws, y, outs = _stack(1, B, Hq, Hkv, d, bs, K, N, [64] * B, 71, poison=False)
-    _run(layers, x, ws, y, outs, packed=packed)
+    _run(layers, x, ws, y, outs, layout=layout)
     cols = np.random.default_rng(0).choice(N, 96, replace=False)
     cols = np.concatenate([cols, [0, 63, 64, N - 1]])
     wsub = oracle.bits_of(ws[0])[:, cols]
@@ -104,6 +104,9 @@ def test_unsupported_gemm_shapes_are_rejected():
     with pytest.raises(kv.KVError) as e:
         _run(layers, x, ws, y[:, :512].contiguous(), outs)          # too few columns for the queries
     assert e.value.status == 1
+    with pytest.raises(kv.KVError) as e:
+        _run(layers, x, ws, y, outs, layout="operand")              # operand order is built for K of 1024 .. 8192 only
+    assert e.value.status == 2
 
 
 def test_layer_stack_configuration_sampled():
@@ -114,7 +117,7 @@ def test_layer_stack_configuration_sampled():
     lens = synth.context_lengths(cfg, synth.config_seed(4))
     _, layers, x, ws, y, outs = _stack(L, cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["bs"], cfg["gemm_k"],
                                        cfg["gemm_n"], lens, synth.config_seed(4), poison=False)
-    _run(layers, x, ws, y, outs, cross=1, packed=True)
+    _run(layers, x, ws, y, outs, cross=1, layout="operand")
     rng = np.random.default_rng(4)
     pairs = np.array([(b, h) for b in rng.choice(cfg["B"], 6, replace=False) for h in rng.choice(cfg["Hq"], 4, replace=False)], np.int32)
     xb = oracle.bits_of(x)
