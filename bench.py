@@ -83,6 +83,33 @@ HEATMAP_MODELS = {               # attention shapes of the paper's four models (
 }
 
 
+def worker_timeline(kv, torch, cases, pd, launches=8):
+    """Where the main kernel's time goes inside a launch: every persistent worker reports the 100 MHz clock at
+    entry, after locating its range and at exit (kv_decode_set_worker_trace).  Percentiles over the workers of
+    the last launch, in microseconds after the first worker's entry."""
+    import numpy as np
+    cfg_d = cases[0]["q"].shape[2]
+    trace = torch.zeros((4096, 4), dtype=torch.int64, device=cases[0]["q"].device)
+    kv.kv_decode_set_worker_trace(trace)
+    try:
+        for i in range(launches):
+            c = cases[i % len(cases)]
+            kv.kv_decode_attn(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], c["out"],
+                              c["scale"], c["num_kv_heads"], c["block_size"], pd)
+        torch.cuda.synchronize()
+    finally:
+        kv.kv_decode_set_worker_trace(None)
+    t = trace.cpu().numpy()
+    t = t[t[:, 3] > 0]                         # workers that had a range
+    t0 = t[:, 0].min()
+    us = lambda col: (t[:, col] - t0) / 100.0
+    pct = lambda a: {f"p{q}": round(float(np.percentile(a, q)), 2) for q in (0, 10, 50, 90, 100)}
+    return {"workers": int(len(t)), "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd, cfg_d),
+            "tiles_per_worker": [int(t[:, 3].min()), int(t[:, 3].max())],
+            "entry_us": pct(us(0)), "range_located_us": pct(us(1)), "exit_us": pct(us(2)),
+            "busy_us": pct((t[:, 2] - t[:, 1]) / 100.0)}
+
+
 def heatmap(kv, torch, synth, dev, pd_on, steps=20, warmup=4):
     """Synthetic counterpart of the paper's batch x sequence-length sweep (Section 4.3, Figure 4): main-kernel time
     with the look-ahead on and off for every (model shape, batch, context) cell; equal context lengths per cell."""
@@ -171,6 +198,8 @@ def main():
     ap.add_argument("--cross-layer-touch", type=int, default=0)
     ap.add_argument("--heatmap", action="store_true",
                     help="print the on/off sweep over model shape x batch x context length and exit")
+    ap.add_argument("--worker-timeline", action="store_true",
+                    help="print the per-worker entry / exit times of one launch of the main kernel and exit")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run plain 1 GiB device copies, so a counter run sees a copy kernel of known traffic")
     args = ap.parse_args()
@@ -222,6 +251,11 @@ def main():
     if args.heatmap:
         print(json.dumps({"heatmap": heatmap(kv, torch, synth, dev, pd_on), "prefetch_distance": pd_on,
                           "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, 128)}), flush=True)
+        return
+    if args.worker_timeline:
+        cfg, cases = make_cases(args.workload)
+        print(json.dumps({"workload": cfg["name"], "prefetch_distance": pd_on,
+                          "worker_timeline": worker_timeline(kv, torch, cases, pd_on)}), flush=True)
         return
     if args.layer_stack_only:
         lms, lkvb, lwb, lcfg, L = layer_stack(kv, torch, synth, dev, args.steps, args.warmup, pd_on, args.cross_layer_touch,

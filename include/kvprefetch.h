@@ -150,6 +150,17 @@ int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
 int kv_profile_enable(int max_calls, int every);
 int kv_profile_read(double* main_ms_sum, int* calls);
 
+/*
+ * Per-worker timeline of the main attention kernel (where inside a launch the time goes: the
+ * paper's Table 1 asks that of its baseline kernel with a profiler; this is the kernel's own
+ * account).  While device memory is registered here, every persistent worker w of a launch with
+ * at most bytes / 32 workers writes four 64-bit words at dev_ptr + 32 w: the constant 100 MHz
+ * clock at entry, after it has located its range, at exit, and the number of tiles it
+ * processed.  NULL/0 unregisters.  The caller owns the memory and reads it after synchronising;
+ * launches with more workers than fit leave it untouched.  Costs two clock reads per worker.
+ */
+int kv_decode_set_worker_trace(void* dev_ptr, size_t bytes);
+
 /* Text of the last error on this thread; never NULL. */
 const char* kv_last_error(void);
 

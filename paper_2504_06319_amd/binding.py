@@ -39,7 +39,7 @@ class KVTensor(ctypes.Structure):
 
 EXPORTS = [
     "kv_decode_attn", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
-    "kv_decode_set_workspace",
+    "kv_decode_set_workspace", "kv_decode_set_worker_trace",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_profile_enable", "kv_profile_read",
 ]
@@ -73,6 +73,8 @@ def load_library():
             lib.kv_layerstack_workspace_bytes.argtypes = [ctypes.c_int] * 3
             lib.kv_decode_set_workspace.restype = ctypes.c_int
             lib.kv_decode_set_workspace.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+            lib.kv_decode_set_worker_trace.restype = ctypes.c_int
+            lib.kv_decode_set_worker_trace.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
             lib.kv_decode_set_waves_per_cu.restype = ctypes.c_int
             lib.kv_decode_set_waves_per_cu.argtypes = [ctypes.c_int]
             lib.kv_decode_get_waves_per_cu.restype = ctypes.c_int
@@ -150,6 +152,17 @@ def kv_decode_workspace_bytes(B: int, Hq: int, d: int, max_context: int, block_s
 
 def kv_layerstack_workspace_bytes(Hq: int, d: int, gemm_n: int) -> int:
     return int(load_library().kv_layerstack_workspace_bytes(Hq, d, gemm_n))
+
+
+def kv_decode_set_worker_trace(buf):
+    """Register an int64 device tensor of shape [workers, 4] for per-worker timestamps, or None to stop."""
+    lib = load_library()
+    if buf is None:
+        _check(lib.kv_decode_set_worker_trace(None, 0))
+        return
+    if buf.dtype != torch.int64 or not buf.is_contiguous():
+        raise KVError(1, "kv_decode_set_worker_trace: a contiguous int64 tensor is needed")
+    _check(lib.kv_decode_set_worker_trace(ctypes.c_void_p(buf.data_ptr()), buf.numel() * 8))
 
 
 def kv_decode_set_waves_per_cu(waves: int):

@@ -266,6 +266,8 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     const int lane = threadIdx.x;
     const int lq = lane / 16, lr = lane % 16;   // lane group (0..3) and index in the group
     const int G = p.G, Hkv = p.Hkv;
+    const bool traced = p.worker_trace != nullptr;            // 100 MHz clock readings for the host, when asked for
+    const unsigned long long t_entry = traced ? wall_clock64() : 0;
     const int max_len = p.MB * BS;
     const_i32_ptr cl = (const_i32_ptr)p.context_lens;
     const_i32_ptr bt = (const_i32_ptr)p.block_tables;
@@ -314,6 +316,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         }
     };
     load_q(ca.b, ca.kvh);
+    const unsigned long long t_scan = traced ? wall_clock64() : 0;
 
     // ---- per-lane byte offsets, loop invariant
     // fetch r of a tile lands kRowsPerLoad rows; this lane lands row t = r * kRowsPerLoad + lane / kChunks at
@@ -494,6 +497,10 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
                 load_q(ca.b, ca.kvh);
             }
         }
+    }
+    if (traced && lane == 0) {
+        unsigned long long* t = p.worker_trace + (int64_t)worker * 4;
+        t[0] = t_entry; t[1] = t_scan; t[2] = wall_clock64(); t[3] = (unsigned long long)(r1 - r0);
     }
 }
 

@@ -24,6 +24,8 @@ int fail(int code, const char* fmt, ...) {
 std::mutex g_ws_mutex;
 void* g_ws_ptr = nullptr;
 size_t g_ws_bytes = 0;
+void* g_trace_ptr = nullptr;         // optional per-worker timestamps (under g_ws_mutex)
+size_t g_trace_bytes = 0;
 std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
 std::atomic<int> g_num_cus{0};       // compute units of the device, read once
 
@@ -159,6 +161,7 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     if (!g_ws_ptr || g_ws_bytes < need)
         return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
     p.partials = (float*)((unsigned char*)g_ws_ptr + kvp::kGemmTicketBytes);
+    p.worker_trace = g_trace_bytes >= (size_t)p.num_workers * 32 ? (unsigned long long*)g_trace_ptr : nullptr;
     return KV_OK;
 }
 
@@ -342,6 +345,16 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     g_ws_ptr = dev_ptr;
     g_ws_bytes = bytes;
+    return KV_OK;
+}
+
+int kv_decode_set_worker_trace(void* dev_ptr, size_t bytes) {
+    if ((dev_ptr == nullptr) != (bytes == 0))
+        return fail(KV_ERR_INVALID, "kv_decode_set_worker_trace: pointer and size must both be set or both be zero");
+    if (((uintptr_t)dev_ptr) % 8) return fail(KV_ERR_INVALID, "kv_decode_set_worker_trace: pointer must be 8-byte aligned");
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    g_trace_ptr = dev_ptr;
+    g_trace_bytes = bytes;
     return KV_OK;
 }
 

@@ -19,6 +19,7 @@ struct AttnParams {
     const int32_t* context_lens;
     void* out;
     float* partials;          // split-KV scratch: unnormalised acc, running max (log2 domain), sum per piece
+    unsigned long long* worker_trace;   // optional: 4 words per worker (clock at entry, after the scan, at exit; tiles); may be null
     int64_t q_stride_b, q_stride_h;
     int64_t kv_stride_blk, kv_stride_h;
     int64_t v_stride_blk, v_stride_h;

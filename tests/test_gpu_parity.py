@@ -253,3 +253,30 @@ def test_full_size_configuration_on_sampled_rows(index):
     sub = got1[torch.from_numpy(pairs[:, 0]).long().to(DEV), torch.from_numpy(pairs[:, 1]).long().to(DEV)]
     compare(sub, want, cfg["name"])
     assert torch.isfinite(got1.float()).all()
+
+
+def test_worker_timeline_accounts_for_every_tile():
+    """Every worker reports its entry / range-located / exit clock readings and its tile count: the counts add
+    up to the tiles of the batch (per kv head), the readings are ordered, and the result is unchanged."""
+    cfg = dict(Hq=8, Hkv=2, d=128, bs=16, dtype="bf16")
+    lens = [700, 0, 33, 1500, 16, 4000, 257, 1]
+    case = synth.make_case(cfg, 97, DEV, poison=True, lens=lens)
+    trace = torch.zeros((4096, 4), dtype=torch.int64, device=DEV)
+    kv.kv_decode_set_worker_trace(trace)
+    try:
+        got = run_hip(case, 2)
+        torch.cuda.synchronize()
+    finally:
+        kv.kv_decode_set_worker_trace(None)
+    t = trace.cpu().numpy()
+    active = t[t[:, 3] > 0]
+    tiles = sum((n + 15) // 16 for n in lens) * cfg["Hkv"]
+    assert active[:, 3].sum() == tiles
+    assert len(active) == min(tiles, 256 * kv.kv_decode_get_waves_per_cu(2, 128))
+    assert (active[:, 0] <= active[:, 1]).all() and (active[:, 1] <= active[:, 2]).all()
+    compare(got, run_oracle(case), "traced launch")
+    # unregistered again: a later launch leaves the buffer alone
+    trace.zero_()
+    run_hip(case, 2)
+    torch.cuda.synchronize()
+    assert int(trace.abs().sum()) == 0
