@@ -8,6 +8,8 @@ from .paged_attention import (  # noqa: F401
     build_oracle,
     paged_attention,
     paged_attention_probs,
+    paged_attention_kv8,
+    fp8e4m3_to_f64,
     oracle_threads,
     bits_of,
     widen_bits,

@@ -58,6 +58,15 @@ def _load():
             lib.oracle_bf16_to_f64.restype = ctypes.c_double
             lib.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
             lib.oracle_num_threads.restype = ctypes.c_int
+            u8p = ctypes.POINTER(ctypes.c_uint8)
+            lib.oracle_fp8e4m3_to_f64.restype = ctypes.c_double
+            lib.oracle_fp8e4m3_to_f64.argtypes = [ctypes.c_uint8]
+            lib.oracle_paged_attention_kv8.restype = ctypes.c_int
+            lib.oracle_paged_attention_kv8.argtypes = [
+                u16p, u8p, u8p, i32p, i32p, f64p,
+                ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double, i32p, ctypes.c_int,
+            ]
             _lib = lib
     return _lib
 
@@ -153,3 +162,43 @@ def paged_attention_probs(q, k_cache, v_cache, block_tables, context_lens, scale
     if rc != 0:
         raise RuntimeError(f"oracle_paged_attention_probs failed with status {rc}")
     return out_row, probs[:n]
+
+
+def fp8e4m3_to_f64(codes) -> np.ndarray:
+    """OCP FP8 E4M3 codes (uint8) -> float64, through the C decoder."""
+    lib = _load()
+    flat = np.ascontiguousarray(codes, dtype=np.uint8).ravel()
+    return np.array([lib.oracle_fp8e4m3_to_f64(int(c)) for c in flat], dtype=np.float64).reshape(np.shape(codes))
+
+
+def paged_attention_kv8(q, k_cache, v_cache, block_tables, context_lens, scale, qdtype, k_scale=1.0,
+                        v_scale=1.0, pairs=None):
+    """fp64 attention output over an FP8 E4M3 cache.
+
+    q [B,Hq,d] as uint16 bits of ``qdtype``; k_cache/v_cache [NBLK,Hkv,bs,d] uint8 codes; the real K is
+    ``k_scale * decode(code)``, V likewise.  Returns like :func:`paged_attention`.
+    """
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    k_cache = np.ascontiguousarray(k_cache, dtype=np.uint8)
+    v_cache = np.ascontiguousarray(v_cache, dtype=np.uint8)
+    block_tables = np.ascontiguousarray(block_tables, dtype=np.int32)
+    context_lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    B, Hq, d, NBLK, Hkv, bs, MB = _check_shapes(q, k_cache, v_cache, block_tables, context_lens)
+    lib = _load()
+    if pairs is None:
+        out = np.empty((B, Hq, d), dtype=np.float64)
+        pp, npairs = None, 0
+    else:
+        pairs = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+        assert ((pairs[:, 0] >= 0) & (pairs[:, 0] < B) & (pairs[:, 1] >= 0) & (pairs[:, 1] < Hq)).all()
+        out = np.empty((pairs.shape[0], d), dtype=np.float64)
+        pp, npairs = _ptr(pairs, ctypes.c_int32), pairs.shape[0]
+    rc = lib.oracle_paged_attention_kv8(
+        _ptr(q, ctypes.c_uint16), _ptr(k_cache, ctypes.c_uint8), _ptr(v_cache, ctypes.c_uint8),
+        _ptr(block_tables, ctypes.c_int32), _ptr(context_lens, ctypes.c_int32),
+        _ptr(out, ctypes.c_double), B, Hq, Hkv, d, bs, MB, NBLK, _DTYPES[qdtype], float(scale),
+        float(k_scale), float(v_scale), pp, npairs,
+    )
+    if rc != 0:
+        raise RuntimeError(f"oracle_paged_attention_kv8 failed with status {rc}")
+    return out

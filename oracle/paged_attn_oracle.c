@@ -154,3 +154,83 @@ int oracle_paged_attention_probs(const uint16_t* q, const uint16_t* k_cache,
     return attend_one(q, k_cache, v_cache, block_tables, context_lens, b, h, Hq, Hkv, d, bs, MB,
                       NBLK, dtype, scale, out_row, probs);
 }
+
+/* ------------------------------------------------------------------------------------------
+ * 8-bit KV cache.  Not in the paper: the same operation (Section 3.1) on a cache whose K and
+ * V elements are OCP FP8 E4M3 codes with one scale per tensor,
+ *     K_b[t][c] = k_scale * e4m3(k_cache[...])      V_b[t][c] = v_scale * e4m3(v_cache[...]),
+ * q and out staying 16-bit.  Halving the bytes per token is what changes; the definition does
+ * not.  Layouts as above with one byte per cache element.
+ * ------------------------------------------------------------------------------------------ */
+
+/* OCP FP8 E4M3 ("fn": no infinities, one NaN code per sign): 1 sign, 4 exponent (bias 7),
+ * 3 mantissa bits.  Checked in the tests on all 256 codes. */
+double oracle_fp8e4m3_to_f64(uint8_t x) {
+    int sign = (x >> 7) & 1;
+    int expo = (x >> 3) & 0xf;
+    int frac = x & 7;
+    double v;
+    if (expo == 0) {
+        v = ldexp((double)frac, -9);              /* zero and subnormals: frac/8 * 2^-6 */
+    } else if (expo == 15 && frac == 7) {
+        v = NAN;
+    } else {
+        v = ldexp(1.0 + (double)frac / 8.0, expo - 7);
+    }
+    return sign ? -v : v;
+}
+
+static int attend_one_kv8(const uint16_t* q, const uint8_t* k_cache, const uint8_t* v_cache,
+                          const int32_t* block_tables, const int32_t* context_lens,
+                          int b, int h, int Hq, int Hkv, int d, int bs, int MB, int64_t NBLK,
+                          int qdtype, double scale, double k_scale, double v_scale, double* out_row) {
+    int n = context_lens[b];
+    for (int c = 0; c < d; ++c) out_row[c] = 0.0;
+    if (n <= 0) return 0;
+    int g = h / (Hq / Hkv);
+    double* s = (double*)malloc((size_t)n * sizeof(double));
+    if (!s) return -1;
+    const uint16_t* qrow = q + ((size_t)b * Hq + h) * d;
+    for (int t = 0; t < n; ++t) {
+        int64_t blk = block_tables[(size_t)b * MB + t / bs];
+        if (blk < 0 || blk >= NBLK) { free(s); return -2; }
+        const uint8_t* krow = k_cache + (((size_t)blk * Hkv + g) * bs + (t % bs)) * d;
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c) dot += widen(qrow[c], qdtype) * (k_scale * oracle_fp8e4m3_to_f64(krow[c]));
+        s[t] = scale * dot;
+    }
+    double mx = s[0];
+    for (int t = 1; t < n; ++t) if (s[t] > mx) mx = s[t];
+    double denom = 0.0;
+    for (int t = 0; t < n; ++t) { s[t] = exp(s[t] - mx); denom += s[t]; }
+    for (int t = 0; t < n; ++t) s[t] /= denom;
+    for (int t = 0; t < n; ++t) {
+        int64_t blk = block_tables[(size_t)b * MB + t / bs];
+        const uint8_t* vrow = v_cache + (((size_t)blk * Hkv + g) * bs + (t % bs)) * d;
+        for (int c = 0; c < d; ++c) out_row[c] += s[t] * (v_scale * oracle_fp8e4m3_to_f64(vrow[c]));
+    }
+    free(s);
+    return 0;
+}
+
+/* As oracle_paged_attention, for an FP8 E4M3 cache; qdtype is the type of q. */
+int oracle_paged_attention_kv8(const uint16_t* q, const uint8_t* k_cache, const uint8_t* v_cache,
+                               const int32_t* block_tables, const int32_t* context_lens,
+                               double* out, int B, int Hq, int Hkv, int d, int bs, int MB,
+                               int64_t NBLK, int qdtype, double scale, double k_scale, double v_scale,
+                               const int32_t* pairs, int npairs) {
+    int total = pairs ? npairs : B * Hq;
+    int status = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < total; ++i) {
+        int b = pairs ? pairs[2 * i] : i / Hq;
+        int h = pairs ? pairs[2 * i + 1] : i % Hq;
+        int rc = attend_one_kv8(q, k_cache, v_cache, block_tables, context_lens, b, h, Hq, Hkv, d, bs,
+                                MB, NBLK, qdtype, scale, k_scale, v_scale, out + (size_t)i * d);
+        if (rc != 0) {
+#pragma omp critical
+            status = rc;
+        }
+    }
+    return status;
+}
