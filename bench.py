@@ -28,8 +28,12 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
     (ms per step by wall clock, main-kernel ms per launch by HIP events on the launch stream)."""
     def step(i):
         c = cases[i % len(cases)]
-        kv.kv_decode_attn(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], c["out"],
-                          c["scale"], c["num_kv_heads"], c["block_size"], pd)
+        if "k_scale" in c:                       # 8-bit cache
+            kv.kv_decode_attn_kv8(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], c["out"],
+                                  c["scale"], c["k_scale"], c["v_scale"], c["num_kv_heads"], c["block_size"], pd)
+        else:
+            kv.kv_decode_attn(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], c["out"],
+                              c["scale"], c["num_kv_heads"], c["block_size"], pd)
     for i in range(warmup):
         step(i)
     every = 4                                  # every 4th launch of the timed region carries an event pair
@@ -198,6 +202,9 @@ def main():
     ap.add_argument("--cross-layer-touch", type=int, default=0)
     ap.add_argument("--heatmap", action="store_true",
                     help="print the on/off sweep over model shape x batch x context length and exit")
+    ap.add_argument("--kv8", action="store_true",
+                    help="time the 8-bit (FP8 E4M3) KV cache entry point on the workload instead (with --no-extra: for "
+                         "profiler runs of that kernel); GB/s then counts the 8-bit bytes")
     ap.add_argument("--worker-timeline", action="store_true",
                     help="print the per-worker entry / exit times of one launch of the main kernel and exit")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -222,19 +229,19 @@ def main():
     if args.waves_per_cu:
         kv.kv_decode_set_waves_per_cu(args.waves_per_cu)
 
-    def make_cases(index, copies=2):
+    def make_cases(index, copies=2, kv8=False):
         cfg = synth.CONFIGS[index]
         out = []
+        make = synth.make_case_kv8 if kv8 else synth.make_case
         for i in range(copies):      # distinct cache copies so no launch re-reads what the last one left in cache
-            c = synth.make_case(cfg, synth.config_seed(index) + 100000 * i, dev,
-                                lens=None if i == 0 else out[0]["lens"])
+            c = make(cfg, synth.config_seed(index) + 100000 * i, dev, lens=None if i == 0 else out[0]["lens"])
             c["out"] = torch.empty_like(c["q"])
             out.append(c)
         return cfg, out
 
-    def measure(index, pd, steps, warmup):
-        cfg, cases = make_cases(index)
-        kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"])
+    def measure(index, pd, steps, warmup, kv8=False):
+        cfg, cases = make_cases(index, kv8=kv8)
+        kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"], 1 if kv8 else 2)
         ms, main_ms = timed_steps(kv, torch, cases, pd, steps, warmup)
         return cfg, cases, kvb, ms, main_ms
 
@@ -247,7 +254,7 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
-    pd_on = args.prefetch_distance if args.prefetch_distance is not None else 2
+    pd_on = args.prefetch_distance if args.prefetch_distance is not None else (1 if args.kv8 else 2)
     if args.heatmap:
         print(json.dumps({"heatmap": heatmap(kv, torch, synth, dev, pd_on), "prefetch_distance": pd_on,
                           "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, 128)}), flush=True)
@@ -265,19 +272,19 @@ def main():
                           "cross_layer_touch": args.cross_layer_touch}), flush=True)
         return
     log(f"[bench] workload {args.workload} prefetch_distance {pd_on}")
-    cfg, cases, kvb, ms, main_ms = measure(args.workload, pd_on, args.steps, args.warmup)
+    cfg, cases, kvb, ms, main_ms = measure(args.workload, pd_on, args.steps, args.warmup, kv8=args.kv8)
     value = kvb / (ms * 1e-3) / 1e9
     achieved = kvb / (main_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg['name']}.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.kv8:
         with open(tpath) as f:
             traffic = json.load(f).get("traffic_bytes_per_launch")
     result = {
         "metric": "decode-attn effective KV GB/s (% of HBM peak), prefetch on vs off; tokens/s",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg["dtype"], "data": "synthetic",
+        "dtype": cfg["dtype"] + (" (q, out) / fp8_e4m3 (KV cache)" if args.kv8 else ""), "data": "synthetic",
         "config": {"workload": cfg["name"], "batch": cfg["B"], "q_heads": cfg["Hq"], "kv_heads": cfg["Hkv"],
                    "head_dim": cfg["d"], "block_size": cfg["bs"],
                    "context_lens": "fixed" if "lens" in cfg else f"uniform{list(cfg['len_range'])}",
@@ -292,6 +299,11 @@ def main():
     }
     log(f"[bench] on: {ms:.4f} ms/step, {value:.0f} GB/s; main kernel {main_ms:.4f} ms")
 
+    if args.kv8:
+        result["config"]["waves_per_cu"] = kv.kv_decode_get_waves_per_cu_kv8(pd_on, cfg["d"])
+        result["roofline"]["kernel"] = "attn_mfma_kernel, 8-bit cache variant"
+        print(json.dumps(result), flush=True)
+        return
     if not args.no_extra:
         _, _, _, ms0, main0 = measure(args.workload, 0, args.steps, args.warmup)
         result["prefetch_off"] = {"prefetch_distance": 0, "waves_per_cu": kv.kv_decode_get_waves_per_cu(0, cfg["d"]),
@@ -325,6 +337,19 @@ def main():
                                     "tokens_per_s": ocfg["B"] / (oms * 1e-3)}
             log(f"[bench] {ocfg['name']}: on {oms:.4f} ms, off {oms0:.4f} ms")
         result["other_workloads"] = others
+        # the same workloads on an 8-bit (FP8 E4M3) KV cache: half the bytes per token; GB/s counts the 8-bit bytes
+        kv8 = {}
+        for idx in (1, 2, 3):
+            torch.cuda.empty_cache()
+            kcfg, _, kkvb, kms, kmain = measure(idx, 1, max(10, args.steps // 2), max(5, args.warmup // 2), kv8=True)
+            _, _, _, kms0, kmain0 = measure(idx, 0, max(10, args.steps // 2), max(5, args.warmup // 2), kv8=True)
+            kv8[kcfg["name"]] = {"prefetch_distance": 1, "waves_per_cu": kv.kv_decode_get_waves_per_cu_kv8(1, kcfg["d"]),
+                                 "kv_bytes_per_step": kkvb, "ms_per_step": kms, "value": kkvb / (kms * 1e-3) / 1e9,
+                                 "unit": "GB/s", "pct_hbm_peak": 100.0 * kkvb / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                 "kernel_ms": kmain, "tokens_per_s": kcfg["B"] / (kms * 1e-3),
+                                 "prefetch_off_ms_per_step": kms0, "prefetch_off_kernel_ms": kmain0}
+            log(f"[bench] {kcfg['name']} 8-bit cache: on {kms:.4f} ms, off {kms0:.4f} ms")
+        result["kv8_cache"] = kv8
         # layer stack (configuration 4): tokens/s of 32 x (dense layer + attention), prefetch on / off, cross-layer touch
         del cases
         torch.cuda.empty_cache()

@@ -36,7 +36,7 @@ typedef enum {
     KV_ERR_WORKSPACE = 4    /* split-KV workspace missing or too small */
 } kv_status;
 
-typedef enum { KV_F16 = 0, KV_BF16 = 1, KV_I32 = 2, KV_F32 = 3 } kv_dtype;
+typedef enum { KV_F16 = 0, KV_BF16 = 1, KV_I32 = 2, KV_F32 = 3, KV_FP8_E4M3 = 4 /* OCP FP8 E4M3 codes, one byte */ } kv_dtype;
 
 /* A device tensor: base pointer, element type, rank, extents and strides (in elements). */
 typedef struct kv_tensor {
@@ -73,6 +73,22 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
                    const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
                    float scale, int num_kv_heads, int block_size, int prefetch_distance,
                    void* stream);
+
+/*
+ * The same operation on an 8-bit KV cache (not in the paper: its Eq. 1 has the element size b as
+ * a parameter, and halving b halves the bytes the kernel is bound by).  k_cache and v_cache hold
+ * OCP FP8 E4M3 codes (dtype KV_FP8_E4M3, one byte per element, same [NBLK, Hkv, bs, d] layout
+ * with the [bs, d] tile dense and outer strides multiples of 16); the values attended to are
+ *     K = k_scale * e4m3(k_cache),   V = v_scale * e4m3(v_cache)      (one positive scale per tensor),
+ * q and out stay f16 or bf16.  The kernel fetches the 8-bit tiles as they are, widens them to
+ * q's type in LDS (exactly: both 16-bit types hold every E4M3 value) and proceeds as
+ * kv_decode_attn; k_scale is folded into the softmax scale, v_scale into the normalisation.
+ * Everything else (arguments, errors, workspace, prefetch_distance) as kv_decode_attn.
+ */
+int kv_decode_attn_kv8(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+                       const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+                       float scale, float k_scale, float v_scale, int num_kv_heads, int block_size,
+                       int prefetch_distance, void* stream);
 
 /*
  * Layer-stack harness: for l = 0 .. num_layers-1
@@ -136,6 +152,9 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
  */
 int kv_decode_set_waves_per_cu(int waves);
 int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
+/* The same for kv_decode_attn_kv8 (ring stages of half the size plus one widened tile pair per worker;
+ * automatic choice at head_dim 128: 12 waves at distance 0, 6 beyond; at head_dim 64: 16 and 12). */
+int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
 
 /*
  * Timing of the main attention kernel with HIP events on the call's own stream (the paper

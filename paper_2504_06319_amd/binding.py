@@ -17,7 +17,9 @@ _lib = None
 _lock = threading.Lock()
 
 KV_F16, KV_BF16, KV_I32, KV_F32 = 0, 1, 2, 3
-_DTYPE_CODES = {torch.float16: KV_F16, torch.bfloat16: KV_BF16, torch.int32: KV_I32, torch.float32: KV_F32}
+KV_FP8_E4M3 = 4
+_DTYPE_CODES = {torch.float16: KV_F16, torch.bfloat16: KV_BF16, torch.int32: KV_I32, torch.float32: KV_F32,
+                torch.float8_e4m3fn: KV_FP8_E4M3}
 KV_MAX_PREFETCH_DISTANCE = 4
 
 
@@ -38,7 +40,7 @@ class KVTensor(ctypes.Structure):
 
 
 EXPORTS = [
-    "kv_decode_attn", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
+    "kv_decode_attn", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
     "kv_decode_set_workspace", "kv_decode_set_worker_trace",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_profile_enable", "kv_profile_read",
@@ -63,6 +65,9 @@ def load_library():
             lib.kv_decode_attn.restype = ctypes.c_int
             lib.kv_decode_attn.argtypes = [T, T, T, T, T, T, ctypes.c_float, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int, ctypes.c_void_p]
+            lib.kv_decode_attn_kv8.restype = ctypes.c_int
+            lib.kv_decode_attn_kv8.argtypes = [T, T, T, T, T, T, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                               ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
             lib.kv_decode_layerstack.restype = ctypes.c_int
             lib.kv_decode_layerstack.argtypes = [ctypes.c_int, T, TT, T, TT, TT, TT, T, T, TT, ctypes.c_float,
                                                  ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -185,6 +190,25 @@ def kv_decode_attn(q, k_cache, v_cache, block_tables, context_lens, out, scale, 
     _check(lib.kv_decode_attn(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
                               int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))))
     return out
+
+
+def kv_decode_attn_kv8(q, k_cache, v_cache, block_tables, context_lens, out, scale, k_scale, v_scale,
+                       num_kv_heads, block_size, prefetch_distance=1, stream=None):
+    """Paged decode attention over an FP8 E4M3 cache (torch.float8_e4m3fn, or uint8 codes)."""
+    lib = load_library()
+    need = kv_decode_workspace_bytes(q.shape[0], q.shape[1], q.shape[2],
+                                     block_tables.shape[1] * block_size, block_size)
+    if need:
+        _ensure_workspace(q.device, need)
+    caches = [c.view(torch.float8_e4m3fn) if c.dtype == torch.uint8 else c for c in (k_cache, v_cache)]
+    descs = [describe(t) for t in (q, caches[0], caches[1], block_tables, context_lens, out)]
+    _check(lib.kv_decode_attn_kv8(*[ctypes.byref(d) for d in descs], float(scale), float(k_scale), float(v_scale), int(num_kv_heads), int(block_size), int(prefetch_distance),
+                                  ctypes.c_void_p(_stream_handle(stream))))
+    return out
+
+
+def kv_decode_get_waves_per_cu_kv8(prefetch_distance: int, head_dim: int = 128) -> int:
+    return int(load_library().kv_decode_get_waves_per_cu_kv8(int(prefetch_distance), int(head_dim)))
 
 
 def _desc_array(tensors):

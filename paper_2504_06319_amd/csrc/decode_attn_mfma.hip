@@ -166,6 +166,33 @@ __device__ __forceinline__ void lds_wait_v(u32x2 (&r)[8]) {
                  : "memory");
 }
 
+// ---- 8-bit KV cache: raw FP8 E4M3 tiles land in the ring as they are in HBM and are widened to the query's
+// 16-bit type into an LDS image of the tile pair that the operand reads below take exactly as they take a 16-bit
+// stage.  These LDS accesses are inline assembly for the same reason as the operand reads.
+__device__ __forceinline__ void lds_read_raw(u32x4& r, uint32_t a) {
+    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(a) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lds_wait_raw(u32x4 (&r)[N]) {
+    if constexpr (N == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) : : "memory");
+    else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]) : : "memory");
+}
+__device__ __forceinline__ void lds_write_b128(uint32_t a, u32x4 v) {
+    asm volatile("ds_write_b128 %0, %1" : : "v"(a), "v"(v) : "memory");
+}
+// four FP8 E4M3 codes of a dword -> four 16-bit values of type E in two dwords (exact: both 16-bit types hold every
+// E4M3 value)
+template <Elem E>
+__device__ __forceinline__ u32x2 widen_fp8x4(uint32_t w) {
+    if constexpr (E == Elem::BF16) {
+        return u32x2{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false)),
+                     __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true))};
+    } else {
+        return u32x2{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false)),
+                     __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true))};
+    }
+}
+
 constexpr int kAuxNonTemporal = 2;                   // cache-policy operand of global_load_lds: nt
 constexpr int kTileTokens = 16;
 constexpr int kMaxWorkers = 4096;
@@ -250,15 +277,21 @@ __device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_wo
     return (int64_t)worker * T / num_workers;
 }
 
-template <Elem E, int D, int BS, int PD>
+// KV8: the caches hold FP8 E4M3 codes (one byte per element); q and out are of type E.
+template <Elem E, int D, int BS, int PD, bool KV8>
 __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     using G_ = Geo<D>;
     constexpr int NS = PD + 1;                  // LDS stages of the wave
     constexpr int TPB = BS / kTileTokens;       // 16-token tiles per KV block
-    constexpr int LPT = G_::kLoadsPerTile;      // wave-wide 1 KB fetches per K (or V) tile
-    constexpr int LOADS = 2 * LPT;              // per tile pair
     constexpr int KJ = G_::kKSteps, CB = G_::kColBlocks;
     constexpr int kRowBytes = G_::kRowBytes, kTileBytes = G_::kTileBytes, kStageBytes = G_::kStageBytes;
+    // what is fetched: the 16-bit tile itself, or the raw 8-bit tile (half the bytes, rows of D bytes)
+    constexpr int kFetchTile = KV8 ? kTileBytes / 2 : kTileBytes;
+    constexpr int kFetchStage = 2 * kFetchTile;
+    constexpr int kElemBytes = KV8 ? 1 : 2;
+    constexpr int LPT = kFetchTile / 1024;      // wave-wide 1 KB fetches per K (or V) tile
+    constexpr int LOADS = 2 * LPT;              // per tile pair
+    constexpr int kImage = NS * kFetchStage;    // KV8: byte offset of the widened tile pair behind the ring
     constexpr int kPartialStride = G_::kPartialStride;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -321,12 +354,32 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     // ---- per-lane byte offsets, loop invariant
     // fetch r of a tile lands kRowsPerLoad rows; this lane lands row t = r * kRowsPerLoad + lane / kChunks at
     // stored chunk lane % kChunks, so it fetches chunk (stored ^ swizzle(t)) of row t
+    // (8-bit cache: the raw tile is copied as it is, fetch r takes bytes 1024 r + 16 lane .. + 16)
     uint32_t koff[LPT], voff[LPT];
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
-        const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
-        koff[r] = t * kRowBytes + ((stored ^ G_::swz_k(t)) << 4);
-        voff[r] = t * kRowBytes + ((stored ^ (2 * G_::swz_v_half(t))) << 4);
+        if constexpr (KV8) {
+            koff[r] = voff[r] = r * 1024 + lane * 16;
+        } else {
+            const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
+            koff[r] = t * kRowBytes + ((stored ^ G_::swz_k(t)) << 4);
+            voff[r] = t * kRowBytes + ((stored ^ (2 * G_::swz_v_half(t))) << 4);
+        }
+    }
+    // 8-bit cache, widening: this lane takes raw 16-byte chunks lane + 64 r of the K tile and of the V tile; chunk
+    // x holds elements 16 (x % (D/16)) .. + 16 of row x / (D/16), which become the two 16-byte chunks 2 (x % (D/16))
+    // and + 1 of that row of the image, stored at the swizzled positions the operand reads expect
+    uint32_t img_k[LPT][2], img_v[LPT][2];
+    if constexpr (KV8) {
+#pragma unroll
+        for (int r = 0; r < LPT; ++r) {
+            const int x = lane + 64 * r, t = x / (D / 16), c2 = 2 * (x % (D / 16));
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                img_k[r][h] = kImage + t * kRowBytes + (((c2 + h) ^ G_::swz_k(t)) << 4);
+                img_v[r][h] = kImage + kTileBytes + t * kRowBytes + (((c2 + h) ^ (2 * G_::swz_v_half(t))) << 4);
+            }
+        }
     }
     // K read for MFMA j: row lr, logical chunk 4j + lq  ->  stored chunk (4j + lq) ^ swizzle(lr)
     uint32_t kread[KJ];
@@ -347,10 +400,10 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     auto issue = [&](const Cursor& c, int stage) {   // asynchronous fetch of one K tile and one V tile into a stage
         int phys = bt[(int64_t)c.b * p.bt_stride_b + c.j / TPB];   // only entries of tiles inside the range are read
         phys = __builtin_amdgcn_readfirstlane(min(max(phys, 0), p.NBLK - 1));
-        const int sub = (c.j % TPB) * kTileBytes;
-        const unsigned char* kt = kcache + ((int64_t)phys * p.kv_stride_blk + (int64_t)c.kvh * p.kv_stride_h) * 2 + sub;
-        const unsigned char* vt_ = vcache + ((int64_t)phys * p.v_stride_blk + (int64_t)c.kvh * p.v_stride_h) * 2 + sub;
-        unsigned char* dst = smem + stage * kStageBytes;
+        const int sub = (c.j % TPB) * kFetchTile;
+        const unsigned char* kt = kcache + ((int64_t)phys * p.kv_stride_blk + (int64_t)c.kvh * p.kv_stride_h) * kElemBytes + sub;
+        const unsigned char* vt_ = vcache + ((int64_t)phys * p.v_stride_blk + (int64_t)c.kvh * p.v_stride_h) * kElemBytes + sub;
+        unsigned char* dst = smem + stage * kFetchStage;
         // every KV byte is used once: the fetches carry the non-temporal hint so that they do not displace
         // anything in L2 / the memory-side cache (the paper's eviction-priority remark, Section 3.3); measured
         // 184 -> 164 us on the Llama-3-8B-shaped batch
@@ -359,7 +412,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             __builtin_amdgcn_global_load_lds(KVP_GLOBAL(kt + koff[r]), KVP_LDS(dst + r * 1024), 16, 0, kAuxNonTemporal);
 #pragma unroll
         for (int r = 0; r < LPT; ++r)
-            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kTileBytes + r * 1024), 16, 0, kAuxNonTemporal);
+            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kFetchTile + r * 1024), 16, 0, kAuxNonTemporal);
     };
 
     float4v o[CB];
@@ -399,7 +452,29 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             }
         }
         asm volatile("" ::: "memory");
-        const uint32_t st = ring_addr + stage * kStageBytes;
+        uint32_t st = ring_addr + stage * kFetchStage;
+        if constexpr (KV8) {
+            // widen the raw tile pair into the image; LDS executes a wave's operations in order, so the operand
+            // reads below see it, and the previous tile's operand reads are long complete
+            u32x4 raw[2 * LPT];
+#pragma unroll
+            for (int r = 0; r < LPT; ++r) {
+                lds_read_raw(raw[r], st + r * 1024 + lane * 16);
+                lds_read_raw(raw[LPT + r], st + kFetchTile + r * 1024 + lane * 16);
+            }
+            lds_wait_raw(raw);
+#pragma unroll
+            for (int r = 0; r < 2 * LPT; ++r) {
+                const uint32_t w0 = raw[r][0], w1 = raw[r][1], w2 = raw[r][2], w3 = raw[r][3];
+                const u32x2 e0 = widen_fp8x4<E>(w0), e1 = widen_fp8x4<E>(w1), e2 = widen_fp8x4<E>(w2), e3 = widen_fp8x4<E>(w3);
+                const uint32_t a0 = e0[0], a1 = e0[1], a2 = e1[0], a3 = e1[1], b0 = e2[0], b1 = e2[1], b2 = e3[0], b3 = e3[1];
+                const u32x4 a = {a0, a1, a2, a3}, b = {b0, b1, b2, b3};
+                const uint32_t* dst = r < LPT ? img_k[r] : img_v[r - LPT];
+                lds_write_b128(ring_addr + dst[0], a);
+                lds_write_b128(ring_addr + dst[1], b);
+            }
+            st = ring_addr + kImage;
+        }
 
         // ---- issue every LDS read of the tile: the K operands, then the transposed V operands
         u32x4 ka[KJ];
@@ -468,7 +543,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             const float lt = group_sum(l);
             if (lr < G) {
                 if (piece_first_j == 0 && unit_end) {           // the whole unit was ours: final rows
-                    const float inv = 1.0f / lt;                // lt > 0: a unit has at least one valid token
+                    const float inv = p.out_scale / lt;         // lt > 0: a unit has at least one valid token
                     uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)ca.b * p.out_stride_b +
                                      (int64_t)(ca.kvh * G + lr) * p.out_stride_h + 4 * lq;
 #pragma unroll
@@ -574,38 +649,40 @@ __global__ __launch_bounds__(D) void attn_finalize_kernel(AttnParams p, int bs) 
     int base = 0;
     for (; np - base > 8; base += 32) batch(base, min(32, np - base), std::integral_constant<int, 32>{});
     if (base < np) batch(base, np - base, std::integral_constant<int, 8>{});
-    orow[c] = pack1<E>(num / den);
+    orow[c] = pack1<E>(num / den * p.out_scale);
 }
 
-template <Elem E, int D, int BS, int PD>
+template <Elem E, int D, int BS, int PD, bool KV8>
 static int launch_one(const AttnParams& p, hipStream_t stream) {
-    const size_t lds = (size_t)(PD + 1) * Geo<D>::kStageBytes;
-    auto kern = attn_mfma_kernel<E, D, BS, PD>;
+    const size_t lds = (size_t)mfma_worker_lds_bytes(PD, D, KV8);
+    auto kern = attn_mfma_kernel<E, D, BS, PD, KV8>;
     hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), lds, stream, p);
     return 0;
 }
 
-template <Elem E, int D, int BS>
+template <Elem E, int D, int BS, bool KV8>
 static int launch_pd(const AttnParams& p, hipStream_t stream) {
     switch (p.prefetch_distance) {
-        case 0: return launch_one<E, D, BS, 0>(p, stream);
-        case 1: return launch_one<E, D, BS, 1>(p, stream);
-        case 2: return launch_one<E, D, BS, 2>(p, stream);
-        case 3: return launch_one<E, D, BS, 3>(p, stream);
-        case 4: return launch_one<E, D, BS, 4>(p, stream);
+        case 0: return launch_one<E, D, BS, 0, KV8>(p, stream);
+        case 1: return launch_one<E, D, BS, 1, KV8>(p, stream);
+        case 2: return launch_one<E, D, BS, 2, KV8>(p, stream);
+        case 3: return launch_one<E, D, BS, 3, KV8>(p, stream);
+        case 4: return launch_one<E, D, BS, 4, KV8>(p, stream);
         default: return -1;
     }
 }
 
-template <Elem E>
+template <Elem E, bool KV8>
 static int launch_shape(const AttnParams& p, int d, int bs, hipStream_t stream) {
-    if (d == 128) return bs == 16 ? launch_pd<E, 128, 16>(p, stream) : launch_pd<E, 128, 32>(p, stream);
-    return bs == 16 ? launch_pd<E, 64, 16>(p, stream) : launch_pd<E, 64, 32>(p, stream);
+    if (d == 128) return bs == 16 ? launch_pd<E, 128, 16, KV8>(p, stream) : launch_pd<E, 128, 32, KV8>(p, stream);
+    return bs == 16 ? launch_pd<E, 64, 16, KV8>(p, stream) : launch_pd<E, 64, 32, KV8>(p, stream);
 }
 
-// LDS bytes one worker (wave) holds at a prefetch distance.
-int mfma_worker_lds_bytes(int prefetch_distance, int d) {
-    return (prefetch_distance + 1) * (d == 128 ? Geo<128>::kStageBytes : Geo<64>::kStageBytes);
+// LDS bytes one worker (wave) holds at a prefetch distance: its ring of fetched tile pairs and, for an 8-bit
+// cache (ring stages of half the size), the widened image of the tile pair being computed.
+int mfma_worker_lds_bytes(int prefetch_distance, int d, bool kv8) {
+    const int stage = d == 128 ? Geo<128>::kStageBytes : Geo<64>::kStageBytes;
+    return kv8 ? (prefetch_distance + 1) * (stage / 2) + stage : (prefetch_distance + 1) * stage;
 }
 
 // Bytes of partial storage for a launch with this many workers.
@@ -689,11 +766,12 @@ int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* s
 }
 
 // Returns 0 or -1 (no such instantiation).
-int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream) {
+int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, bool kv8, hipStream_t stream) {
     if (p.num_workers < 1 || p.num_workers > kMaxWorkers) return -1;
     if (d != 64 && d != 128) return -1;
     if (bs != 16 && bs != 32) return -1;
-    return elem == (int)Elem::F16 ? launch_shape<Elem::F16>(p, d, bs, stream) : launch_shape<Elem::BF16>(p, d, bs, stream);
+    if (kv8) return elem == (int)Elem::F16 ? launch_shape<Elem::F16, true>(p, d, bs, stream) : launch_shape<Elem::BF16, true>(p, d, bs, stream);
+    return elem == (int)Elem::F16 ? launch_shape<Elem::F16, false>(p, d, bs, stream) : launch_shape<Elem::BF16, false>(p, d, bs, stream);
 }
 
 }  // namespace kvp

@@ -3,6 +3,8 @@
 #include "../../include/kvprefetch.h"
 #include "kv_common.h"
 
+#include <cmath>
+
 #include <atomic>
 #include <cstdarg>
 #include <cstdio>
@@ -48,13 +50,18 @@ int num_cus() {
 // unit at any time; beyond that throughput falls again (measured: 64-96 KB in flight costs 4-8 %).  A wave
 // keeps max(1, distance) tile pairs of 8 KB (head_dim 128) or 4 KB (head_dim 64) in flight, so deep look-ahead
 // wants few waves and no look-ahead wants many; head_dim 64 needs at least four waves to keep up with the
-// arithmetic of its smaller tiles.  Always capped by the LDS the rings need.
-int waves_per_cu(int prefetch_distance, int d) {
-    const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance, d);
+// arithmetic of its smaller tiles.  An 8-bit cache halves the bytes of a tile and adds the widening to the
+// arithmetic, so it wants more waves for both reasons (measured: 12 waves without look-ahead and 6 with at head_dim 128,
+// 16 and 12 at head_dim 64; 10 or 13 waves, uneven over the four SIMDs, are 25 % slower, so its count is kept even).  Always
+// capped by the LDS the rings need.
+int waves_per_cu(int prefetch_distance, int d, bool kv8) {
+    const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance, d, kv8);
     int w = g_waves_per_cu.load();
     if (w <= 0) {
-        if (d == 128) w = prefetch_distance <= 1 ? 6 : 2;
+        if (kv8) w = d == 128 ? (prefetch_distance == 0 ? 12 : 6) : (prefetch_distance == 0 ? 16 : 12);
+        else if (d == 128) w = prefetch_distance <= 1 ? 6 : 2;
         else w = prefetch_distance <= 1 ? 8 : 4;
+        if (kv8 && w > lds_limit) w = lds_limit > 8 ? (lds_limit & ~3) : (lds_limit & ~1);   // even over the four SIMDs
     }
     w = w < lds_limit ? w : lds_limit;
     w = w < kMaxWavesPerCU ? w : kMaxWavesPerCU;
@@ -78,11 +85,13 @@ bool dense_tile(const kv_tensor* t) {   // [NBLK, Hkv, bs, d] with the [bs, d] t
 struct Resolved {
     kvp::AttnParams p;
     int elem, d, bs;
+    bool kv8;
 };
 
 int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
             const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
-            float scale, int num_kv_heads, int block_size, int prefetch_distance, Resolved* r) {
+            float scale, int num_kv_heads, int block_size, int prefetch_distance, Resolved* r,
+            bool kv8 = false, float k_scale = 1.0f, float v_scale = 1.0f) {
     if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !out)
         return fail(KV_ERR_INVALID, "kv_decode_attn: null tensor descriptor");
     if (!q->data || !k_cache->data || !v_cache->data || !block_tables->data || !context_lens->data || !out->data)
@@ -92,8 +101,14 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
         return fail(KV_ERR_INVALID, "kv_decode_attn: wrong rank (q,out 3; caches 4; block_tables 2; context_lens 1)");
     if (q->dtype != KV_F16 && q->dtype != KV_BF16)
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: q dtype %d is not f16/bf16", q->dtype);
-    if (k_cache->dtype != q->dtype || v_cache->dtype != q->dtype || out->dtype != q->dtype)
+    if (kv8) {
+        if (k_cache->dtype != KV_FP8_E4M3 || v_cache->dtype != KV_FP8_E4M3 || out->dtype != q->dtype)
+            return fail(KV_ERR_INVALID, "kv_decode_attn_kv8: caches must be FP8 E4M3, out of q's dtype");
+        if (!(k_scale > 0.0f) || !(v_scale > 0.0f) || !std::isfinite(k_scale) || !std::isfinite(v_scale))
+            return fail(KV_ERR_INVALID, "kv_decode_attn_kv8: k_scale and v_scale must be positive and finite");
+    } else if (k_cache->dtype != q->dtype || v_cache->dtype != q->dtype || out->dtype != q->dtype) {
         return fail(KV_ERR_INVALID, "kv_decode_attn: q, k_cache, v_cache and out must share one dtype");
+    }
     if (block_tables->dtype != KV_I32 || context_lens->dtype != KV_I32)
         return fail(KV_ERR_INVALID, "kv_decode_attn: block_tables and context_lens must be int32");
     const int64_t B = q->shape[0], Hq = q->shape[1], d = q->shape[2];
@@ -128,12 +143,13 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE)
         return fail(KV_ERR_INVALID, "kv_decode_attn: prefetch_distance %d outside 0..%d", prefetch_distance, KV_MAX_PREFETCH_DISTANCE);
     // 128-bit loads need 16-byte aligned rows
-    auto aligned = [](const kv_tensor* t, int nstr) {
+    auto aligned = [](const kv_tensor* t, int nstr, int elems_per_16_bytes) {
         if (((uintptr_t)t->data) % 16) return false;
-        for (int i = 0; i < nstr; ++i) if (t->stride[i] % 8) return false;
+        for (int i = 0; i < nstr; ++i) if (t->stride[i] % elems_per_16_bytes) return false;
         return true;
     };
-    if (!aligned(q, 2) || !aligned(k_cache, 2) || !aligned(v_cache, 2) || !aligned(out, 2))
+    const int cache_elems = kv8 ? 16 : 8;
+    if (!aligned(q, 2, 8) || !aligned(k_cache, 2, cache_elems) || !aligned(v_cache, 2, cache_elems) || !aligned(out, 2, 8))
         return fail(KV_ERR_INVALID, "kv_decode_attn: data pointers and outer strides must be 16-byte aligned");
 
     const int64_t MB = block_tables->shape[1];
@@ -150,11 +166,12 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.B = (int)B; p.Hq = (int)Hq; p.Hkv = num_kv_heads; p.G = G;
     p.MB = (int)MB; p.NBLK = (int)k_cache->shape[0];
     p.prefetch_distance = prefetch_distance;
-    p.scale_log2e = scale * kvp::kLog2e;
-    r->elem = q->dtype; r->d = (int)d; r->bs = block_size;
+    p.scale_log2e = scale * kvp::kLog2e * (kv8 ? k_scale : 1.0f);
+    p.out_scale = kv8 ? v_scale : 1.0f;
+    r->elem = q->dtype; r->d = (int)d; r->bs = block_size; r->kv8 = kv8;
     const int cus = num_cus();
     if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
-    const int nw = cus * waves_per_cu(prefetch_distance, (int)d);
+    const int nw = cus * waves_per_cu(prefetch_distance, (int)d, kv8);
     p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
     const size_t need = kvp::kGemmTicketBytes + kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
     std::lock_guard<std::mutex> lock(g_ws_mutex);
@@ -192,7 +209,7 @@ int run_attn(const Resolved& r, hipStream_t stream) {
     if (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity && (g_prof_seen++ % g_prof_every) == 0) slot = g_prof_calls++;
     prof_lock.unlock();
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), stream);
-    if (kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, stream) != 0)
+    if (kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, r.kv8, stream) != 0)
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);
@@ -211,6 +228,17 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
     Resolved r;
     if (int rc = resolve(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
                          block_size, prefetch_distance, &r))
+        return rc;
+    return run_attn(r, (hipStream_t)stream);
+}
+
+int kv_decode_attn_kv8(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+                       const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+                       float scale, float k_scale, float v_scale, int num_kv_heads, int block_size,
+                       int prefetch_distance, void* stream) {
+    Resolved r;
+    if (int rc = resolve(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
+                         block_size, prefetch_distance, &r, true, k_scale, v_scale))
         return rc;
     return run_attn(r, (hipStream_t)stream);
 }
@@ -367,7 +395,12 @@ int kv_decode_set_waves_per_cu(int waves) {
 
 int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim) {
     if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE || (head_dim != 64 && head_dim != 128)) return 0;
-    return waves_per_cu(prefetch_distance, head_dim);
+    return waves_per_cu(prefetch_distance, head_dim, false);
+}
+
+int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim) {
+    if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE || (head_dim != 64 && head_dim != 128)) return 0;
+    return waves_per_cu(prefetch_distance, head_dim, true);
 }
 
 int kv_profile_enable(int max_calls, int every) {

@@ -122,6 +122,22 @@ def make_case(cfg: dict, seed: int, device="cpu", poison: bool = False, table_wi
     )
 
 
+def to_fp8_codes(x: torch.Tensor, scale: float) -> torch.Tensor:
+    """Nearest OCP FP8 E4M3 codes (uint8) of x / scale; NaN stays NaN (code 0x7f / 0xff)."""
+    return (x.to(torch.float32) / scale).to(torch.float8_e4m3fn).view(torch.uint8)
+
+
+def make_case_kv8(cfg: dict, seed: int, device="cpu", poison: bool = False, lens=None, k_scale: float = 1.0,
+                  v_scale: float = 1.0, table_width: int | None = None) -> dict:
+    """As :func:`make_case` with the caches quantised to FP8 E4M3 codes: the values attended to are
+    ``k_scale * decode(k_cache)`` and ``v_scale * decode(v_cache)``."""
+    c = make_case(cfg, seed, device, poison=poison, table_width=table_width, lens=lens)
+    c["k_cache"] = to_fp8_codes(c["k_cache"], k_scale)
+    c["v_cache"] = to_fp8_codes(c["v_cache"], v_scale)
+    c["k_scale"], c["v_scale"] = float(k_scale), float(v_scale)
+    return c
+
+
 def kv_bytes(lens, Hkv: int, d: int, elem_bytes: int = 2) -> int:
     """Algorithmic K+V bytes one attention call must move."""
     return int(np.maximum(np.asarray(lens, dtype=np.int64), 0).sum()) * Hkv * d * 2 * elem_bytes

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "kvprefetch.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(kv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(kv_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -61,8 +61,12 @@ def test_waves_per_cu_follow_the_lds_budget():
     assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [8, 8, 4, 4, 4]
     # an explicit request is capped by LDS: a worker's ring is (distance + 1) x 8 KB at head_dim 128 (4 KB at
     # 64), a compute unit has 160 KB
+    # 8-bit cache: ring stages of half the size plus one widened tile pair; more waves, kept even over the SIMDs
+    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [12, 6, 6, 6, 4]
+    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 64) for d in range(5)] == [16, 12, 12, 12, 8]
     kv.kv_decode_set_waves_per_cu(16)
     try:
+        assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [13, 10, 8, 6, 5]
         assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [16, 10, 6, 5, 4]
         assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [16, 16, 13, 10, 8]
         with pytest.raises(kv.KVError):
