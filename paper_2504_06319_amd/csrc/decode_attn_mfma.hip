@@ -35,7 +35,11 @@
 // global_load_lds_dwordx4 (lane i of load r lands at r*1024 + i*16).  Bank conflicts are
 // avoided by permuting which 16-byte chunk of a row each lane fetches: with C = d/8 chunks per
 // row and s = row / (16/C), K rows are stored with chunk index XOR (s mod C), V rows with
-// chunk index XOR 2*(s mod C/2) (d = 128: XOR row and XOR 2*(row mod 8)).
+// chunk index XOR (2*(s mod C/2) XOR (s mod 2)) (d = 128: XOR row, and XOR 2*(row mod 8) XOR (row mod 2)).
+//
+// 8-bit cache (KV8): the ring holds the raw FP8 E4M3 tiles (half the bytes); before the operand
+// reads a wave widens the current tile pair to the query's 16-bit type into one more stage laid out
+// exactly as above, so everything downstream is shared with the 16-bit path.
 #include "kv_common.h"
 
 #include <type_traits>
@@ -211,7 +215,12 @@ struct Geo {
     static constexpr int kColBlocks = D / 16;                      // 16-column blocks of the output
     static constexpr int kPartialStride = D + 4;                   // floats per partial row: acc, max, sum, 2 pad (16-byte rows)
     __host__ __device__ static constexpr int swz_k(int row) { return (row / kSwzShift) % kChunks; }
-    __host__ __device__ static constexpr int swz_v_half(int row) { return (row / kSwzShift) % (kChunks / 2); }   // V swizzle / 2
+    // V swizzle of the 16-byte chunk index: the even part moves the 32-byte block a transpose read takes, the low
+    // bit swaps the halves of that block on every other swizzle row so that the widening writes of an 8-bit cache
+    // (two adjacent chunks per lane) spread over all banks as well
+    __host__ __device__ static constexpr int swz_v(int row) {
+        return 2 * ((row / kSwzShift) % (kChunks / 2)) ^ ((row / kSwzShift) & 1);
+    }
 };
 
 // Position of a worker inside the flat tile space; every field is wave-uniform.
@@ -363,7 +372,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         } else {
             const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
             koff[r] = t * kRowBytes + ((stored ^ G_::swz_k(t)) << 4);
-            voff[r] = t * kRowBytes + ((stored ^ (2 * G_::swz_v_half(t))) << 4);
+            voff[r] = t * kRowBytes + ((stored ^ G_::swz_v(t)) << 4);
         }
     }
     // 8-bit cache, widening: this lane takes raw 16-byte chunks lane + 64 r of the K tile and of the V tile; chunk
@@ -377,7 +386,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 img_k[r][h] = kImage + t * kRowBytes + (((c2 + h) ^ G_::swz_k(t)) << 4);
-                img_v[r][h] = kImage + kTileBytes + t * kRowBytes + (((c2 + h) ^ (2 * G_::swz_v_half(t))) << 4);
+                img_v[r][h] = kImage + kTileBytes + t * kRowBytes + (((c2 + h) ^ G_::swz_v(t)) << 4);
             }
         }
     }
@@ -385,13 +394,13 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     uint32_t kread[KJ];
 #pragma unroll
     for (int j = 0; j < KJ; ++j) kread[j] = lr * kRowBytes + (((4 * j + lq) ^ G_::swz_k(lr)) << 4);
-    // V transpose read for column block cb: row lane/4, logical byte 32 cb + 8 (lane % 4); the swizzle is even, so
-    // it acts on the 32-byte block index
+    // V transpose read for column block cb: row lane/4, logical byte 32 cb + 8 (lane % 4), i.e. half lane % 2 of
+    // logical chunk 2 cb + (lane % 4) / 2; the four lanes of a row stay inside one 32-byte block
     const int vt = lane / 4;
     uint32_t vread[CB];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
-        vread[cb] = kTileBytes + vt * kRowBytes + ((cb ^ G_::swz_v_half(vt)) << 5) + ((lane % 4) << 3);
+        vread[cb] = kTileBytes + vt * kRowBytes + (((2 * cb + (lane % 4) / 2) ^ G_::swz_v(vt)) << 4) + ((lane % 2) << 3);
 
     const uint32_t ring_addr = (uint32_t)(uintptr_t)KVP_LDS(smem);      // LDS byte address of the ring
     const unsigned char* kcache = reinterpret_cast<const unsigned char*>(p.k_cache);
