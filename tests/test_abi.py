@@ -129,6 +129,32 @@ def test_scalar_arguments_are_checked():
     assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], bs=8) == 2
 
 
+def test_kv8_entry_point_checks_cache_type_scales_and_alignment():
+    lib = kv.load_library()
+    ref = ctypes.byref
+    f8 = torch.float8_e4m3fn
+
+    def call(a, ks=1.0, vs=1.0):
+        return lib.kv_decode_attn_kv8(ref(a["q"]), ref(a["k"]), ref(a["v"]), ref(a["bt"]), ref(a["cl"]), ref(a["out"]),
+                                      0.1, ks, vs, 2, 16, 1, None)
+
+    a = _good()
+    assert call(a) == 1 and "FP8" in kv.kv_last_error()                    # 16-bit caches
+    a.update(k=_fake((10, 2, 16, 128), f8), v=_fake((10, 2, 16, 128), f8))
+    for ks, vs in ((0.0, 1.0), (1.0, -1.0), (float("inf"), 1.0), (1.0, float("nan"))):
+        assert call(a, ks, vs) == 1 and "scale" in kv.kv_last_error()
+    a["k"].stride[0] = 2 * 16 * 128 + 8                                    # block stride not a multiple of 16 bytes
+    assert call(a) == 1 and "aligned" in kv.kv_last_error()
+    a = _good()
+    a.update(k=_fake((10, 2, 16, 128), f8), v=_fake((10, 2, 16, 128), f8))
+    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"]) == 1  # 8-bit caches through the 16-bit entry point
+    # valid arguments get past validation: without a GPU the device query fails (3), with one the missing
+    # workspace is reported (4); nothing is launched either way
+    lib.kv_decode_set_workspace(None, 0)
+    binding._registered = (0, 0)
+    assert call(a) in (3, 4)
+
+
 def test_workspace_registration_arguments_are_checked():
     lib = kv.load_library()
     assert lib.kv_decode_set_workspace(None, 0) == 0
