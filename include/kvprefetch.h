@@ -81,8 +81,8 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
  * with the [bs, d] tile dense and outer strides multiples of 16); the values attended to are
  *     K = k_scale * e4m3(k_cache),   V = v_scale * e4m3(v_cache)      (one positive scale per tensor),
  * q and out stay f16 or bf16.  The kernel fetches the 8-bit tiles as they are, widens them to
- * q's type in LDS (exactly: both 16-bit types hold every E4M3 value) and proceeds as
- * kv_decode_attn; k_scale is folded into the softmax scale, v_scale into the normalisation.
+ * q's type on the way to the matrix cores (exactly: both 16-bit types hold every E4M3 value) and
+ * proceeds as kv_decode_attn; k_scale is folded into the softmax scale, v_scale into the normalisation.
  * Everything else (arguments, errors, workspace, prefetch_distance) as kv_decode_attn.
  */
 int kv_decode_attn_kv8(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
@@ -152,7 +152,7 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
  */
 int kv_decode_set_waves_per_cu(int waves);
 int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
-/* The same for kv_decode_attn_kv8 (ring stages of half the size plus one widened tile pair per worker;
+/* The same for kv_decode_attn_kv8 (ring stages of half the size plus one widened V tile per worker;
  * automatic choice at head_dim 128: 12 waves at distance 0, 6 beyond; at head_dim 64: 16 and 12). */
 int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
 

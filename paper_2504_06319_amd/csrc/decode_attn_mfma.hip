@@ -37,9 +37,11 @@
 // row and s = row / (16/C), K rows are stored with chunk index XOR (s mod C), V rows with
 // chunk index XOR (2*(s mod C/2) XOR (s mod 2)) (d = 128: XOR row, and XOR 2*(row mod 8) XOR (row mod 2)).
 //
-// 8-bit cache (KV8): the ring holds the raw FP8 E4M3 tiles (half the bytes); before the operand
-// reads a wave widens the current tile pair to the query's 16-bit type into one more stage laid out
-// exactly as above, so everything downstream is shared with the 16-bit path.
+// 8-bit cache (KV8): the ring holds the raw FP8 E4M3 tiles (half the bytes).  The K operand of an
+// MFMA is eight codes per lane read straight from the raw tile (chunk-swizzled on the fetch side for
+// that read) and widened to the query's 16-bit type in registers; the V tile is widened into one
+// more LDS tile laid out exactly as above, because the transpose read works on 16-bit elements.
+// Everything downstream is shared with the 16-bit path.
 #include "kv_common.h"
 
 #include <type_traits>
@@ -176,10 +178,14 @@ __device__ __forceinline__ void lds_wait_v(u32x2 (&r)[8]) {
 __device__ __forceinline__ void lds_read_raw(u32x4& r, uint32_t a) {
     asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(a) : "memory");
 }
-template <int N>
-__device__ __forceinline__ void lds_wait_raw(u32x4 (&r)[N]) {
-    if constexpr (N == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) : : "memory");
-    else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]) : : "memory");
+__device__ __forceinline__ void lds_read_raw64(u32x2& r, uint32_t a) {
+    asm volatile("ds_read_b64 %0, %1" : "=v"(r) : "v"(a) : "memory");
+}
+__device__ __forceinline__ void lds_wait_raw(u32x2 (&k)[4], u32x4 (&v)[2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(k[0]), "+v"(k[1]), "+v"(k[2]), "+v"(k[3]), "+v"(v[0]), "+v"(v[1]) : : "memory");
+}
+__device__ __forceinline__ void lds_wait_raw(u32x2 (&k)[2], u32x4 (&v)[1]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(k[0]), "+v"(k[1]), "+v"(v[0]) : : "memory");
 }
 __device__ __forceinline__ void lds_write_b128(uint32_t a, u32x4 v) {
     asm volatile("ds_write_b128 %0, %1" : : "v"(a), "v"(v) : "memory");
@@ -300,7 +306,10 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     constexpr int kElemBytes = KV8 ? 1 : 2;
     constexpr int LPT = kFetchTile / 1024;      // wave-wide 1 KB fetches per K (or V) tile
     constexpr int LOADS = 2 * LPT;              // per tile pair
-    constexpr int kImage = NS * kFetchStage;    // KV8: byte offset of the widened tile pair behind the ring
+    constexpr int kImage = NS * kFetchStage;    // KV8: byte offset of the widened V tile behind the ring
+    // KV8, raw K tile: rows of D bytes, RP rows per 256 bytes of LDS, CR 16-byte chunks per row; chunk index XOR
+    // (row / RP) % CR spreads the 8-byte operand reads of 16 rows over all banks
+    constexpr int kRawRP = 256 / D, kRawCR = D / 16;
     constexpr int kPartialStride = G_::kPartialStride;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -363,32 +372,38 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     // ---- per-lane byte offsets, loop invariant
     // fetch r of a tile lands kRowsPerLoad rows; this lane lands row t = r * kRowsPerLoad + lane / kChunks at
     // stored chunk lane % kChunks, so it fetches chunk (stored ^ swizzle(t)) of row t
-    // (8-bit cache: the raw tile is copied as it is, fetch r takes bytes 1024 r + 16 lane .. + 16)
+    // (8-bit cache: the raw V tile is copied as it is, fetch r takes bytes 1024 r + 16 lane .. + 16; the raw K
+    // tile is chunk-swizzled for the operand reads)
     uint32_t koff[LPT], voff[LPT];
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
         if constexpr (KV8) {
-            koff[r] = voff[r] = r * 1024 + lane * 16;
+            const int x = lane + 64 * r, t = x / kRawCR, stored = x % kRawCR;
+            koff[r] = t * D + ((stored ^ ((t / kRawRP) % kRawCR)) << 4);
+            voff[r] = r * 1024 + lane * 16;
         } else {
             const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
             koff[r] = t * kRowBytes + ((stored ^ G_::swz_k(t)) << 4);
             voff[r] = t * kRowBytes + ((stored ^ G_::swz_v(t)) << 4);
         }
     }
-    // 8-bit cache, widening: this lane takes raw 16-byte chunks lane + 64 r of the K tile and of the V tile; chunk
-    // x holds elements 16 (x % (D/16)) .. + 16 of row x / (D/16), which become the two 16-byte chunks 2 (x % (D/16))
-    // and + 1 of that row of the image, stored at the swizzled positions the operand reads expect
-    uint32_t img_k[LPT][2], img_v[LPT][2];
+    // 8-bit cache, widening of V: this lane takes raw 16-byte chunks lane + 64 r of the V tile; chunk x holds
+    // elements 16 (x % (D/16)) .. + 16 of row x / (D/16), which become the two 16-byte chunks 2 (x % (D/16)) and + 1
+    // of that row of the image, stored at the swizzled positions the transpose reads expect.  (The image keeps
+    // the place of the V tile in a 16-bit stage: its base is kImage - kTileBytes.)
+    uint32_t img_v[LPT][2];
+    // 8-bit cache, K operand of MFMA j straight from the raw tile: row lr, bytes 32 j + 8 lq .. + 8
+    uint32_t kraw[KJ];
     if constexpr (KV8) {
 #pragma unroll
         for (int r = 0; r < LPT; ++r) {
             const int x = lane + 64 * r, t = x / (D / 16), c2 = 2 * (x % (D / 16));
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                img_k[r][h] = kImage + t * kRowBytes + (((c2 + h) ^ G_::swz_k(t)) << 4);
-                img_v[r][h] = kImage + kTileBytes + t * kRowBytes + (((c2 + h) ^ G_::swz_v(t)) << 4);
-            }
+            for (int h = 0; h < 2; ++h) img_v[r][h] = kImage + t * kRowBytes + (((c2 + h) ^ G_::swz_v(t)) << 4);
         }
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            kraw[j] = lr * D + (((2 * j + lq / 2) ^ ((lr / kRawRP) % kRawCR)) << 4) + ((lq % 2) << 3);
     }
     // K read for MFMA j: row lr, logical chunk 4j + lq  ->  stored chunk (4j + lq) ^ swizzle(lr)
     uint32_t kread[KJ];
@@ -462,41 +477,50 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         }
         asm volatile("" ::: "memory");
         uint32_t st = ring_addr + stage * kFetchStage;
+        u32x4 ka[KJ];
+        u32x2 va[CB];
         if constexpr (KV8) {
-            // widen the raw tile pair into the image; LDS executes a wave's operations in order, so the operand
-            // reads below see it, and the previous tile's operand reads are long complete
-            u32x4 raw[2 * LPT];
+            // raw K operands (8 codes per lane and MFMA) and the raw V tile, then V widened into the image; LDS
+            // executes a wave's operations in order, so the transpose reads below see it, and the previous tile's
+            // reads are long complete
+            u32x2 kr[KJ];
+            u32x4 raw[LPT];
+#pragma unroll
+            for (int j = 0; j < KJ; ++j) lds_read_raw64(kr[j], st + kraw[j]);
+#pragma unroll
+            for (int r = 0; r < LPT; ++r) lds_read_raw(raw[r], st + kFetchTile + r * 1024 + lane * 16);
+            lds_wait_raw(kr, raw);
 #pragma unroll
             for (int r = 0; r < LPT; ++r) {
-                lds_read_raw(raw[r], st + r * 1024 + lane * 16);
-                lds_read_raw(raw[LPT + r], st + kFetchTile + r * 1024 + lane * 16);
-            }
-            lds_wait_raw(raw);
-#pragma unroll
-            for (int r = 0; r < 2 * LPT; ++r) {
                 const uint32_t w0 = raw[r][0], w1 = raw[r][1], w2 = raw[r][2], w3 = raw[r][3];
                 const u32x2 e0 = widen_fp8x4<E>(w0), e1 = widen_fp8x4<E>(w1), e2 = widen_fp8x4<E>(w2), e3 = widen_fp8x4<E>(w3);
                 const uint32_t a0 = e0[0], a1 = e0[1], a2 = e1[0], a3 = e1[1], b0 = e2[0], b1 = e2[1], b2 = e3[0], b3 = e3[1];
-                const u32x4 a = {a0, a1, a2, a3}, b = {b0, b1, b2, b3};
-                const uint32_t* dst = r < LPT ? img_k[r] : img_v[r - LPT];
-                lds_write_b128(ring_addr + dst[0], a);
-                lds_write_b128(ring_addr + dst[1], b);
+                lds_write_b128(ring_addr + img_v[r][0], u32x4{a0, a1, a2, a3});
+                lds_write_b128(ring_addr + img_v[r][1], u32x4{b0, b1, b2, b3});
             }
-            st = ring_addr + kImage;
+            st = ring_addr + kImage - kTileBytes;
+#pragma unroll
+            for (int c4 = 0; c4 < CB; c4 += 4)
+                lds_read_tr16_x4(va[c4], va[c4 + 1], va[c4 + 2], va[c4 + 3], st + vread[c4], st + vread[c4 + 1], st + vread[c4 + 2], st + vread[c4 + 3]);
+#pragma unroll
+            for (int j = 0; j < KJ; ++j) {
+                const uint32_t w0 = kr[j][0], w1 = kr[j][1];
+                const u32x2 e0 = widen_fp8x4<E>(w0), e1 = widen_fp8x4<E>(w1);
+                const uint32_t a0 = e0[0], a1 = e0[1], a2 = e1[0], a3 = e1[1];
+                ka[j] = u32x4{a0, a1, a2, a3};
+            }
+        } else {
+            // ---- issue every LDS read of the tile: the K operands, then the transposed V operands
+            if constexpr (KJ == 4) lds_read_b128_x4(ka[0], ka[1], ka[2], ka[3], st + kread[0], st + kread[1], st + kread[2], st + kread[3]);
+            else lds_read_b128_x2(ka[0], ka[1], st + kread[0], st + kread[1]);
+#pragma unroll
+            for (int c4 = 0; c4 < CB; c4 += 4)
+                lds_read_tr16_x4(va[c4], va[c4 + 1], va[c4 + 2], va[c4 + 3], st + vread[c4], st + vread[c4 + 1], st + vread[c4 + 2], st + vread[c4 + 3]);
+            if constexpr (KJ == 4) lds_wait_k<CB>(ka[0], ka[1], ka[2], ka[3]);
+            else lds_wait_k<CB>(ka[0], ka[1]);
         }
 
-        // ---- issue every LDS read of the tile: the K operands, then the transposed V operands
-        u32x4 ka[KJ];
-        u32x2 va[CB];
-        if constexpr (KJ == 4) lds_read_b128_x4(ka[0], ka[1], ka[2], ka[3], st + kread[0], st + kread[1], st + kread[2], st + kread[3]);
-        else lds_read_b128_x2(ka[0], ka[1], st + kread[0], st + kread[1]);
-#pragma unroll
-        for (int c4 = 0; c4 < CB; c4 += 4)
-            lds_read_tr16_x4(va[c4], va[c4 + 1], va[c4 + 2], va[c4 + 3], st + vread[c4], st + vread[c4 + 1], st + vread[c4 + 2], st + vread[c4 + 3]);
-
         // ---- S^T = K Q^T once the K operands are back (the CB reads of V may still be outstanding)
-        if constexpr (KJ == 4) lds_wait_k<CB>(ka[0], ka[1], ka[2], ka[3]);
-        else lds_wait_k<CB>(ka[0], ka[1]);
         // two independent accumulation chains: a dependent MFMA waits for the previous one's full latency
         float4v sacc = mfma_k32<E>(ka[0], qb[0], float4v{0.f, 0.f, 0.f, 0.f});
         float4v sacc1 = mfma_k32<E>(ka[1], qb[1], float4v{0.f, 0.f, 0.f, 0.f});
@@ -688,10 +712,10 @@ static int launch_shape(const AttnParams& p, int d, int bs, hipStream_t stream) 
 }
 
 // LDS bytes one worker (wave) holds at a prefetch distance: its ring of fetched tile pairs and, for an 8-bit
-// cache (ring stages of half the size), the widened image of the tile pair being computed.
+// cache (ring stages of half the size), the widened image of the V tile being computed.
 int mfma_worker_lds_bytes(int prefetch_distance, int d, bool kv8) {
     const int stage = d == 128 ? Geo<128>::kStageBytes : Geo<64>::kStageBytes;
-    return kv8 ? (prefetch_distance + 1) * (stage / 2) + stage : (prefetch_distance + 1) * stage;
+    return kv8 ? (prefetch_distance + 2) * (stage / 2) : (prefetch_distance + 1) * stage;
 }
 
 // Bytes of partial storage for a launch with this many workers.
