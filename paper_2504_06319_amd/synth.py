@@ -128,10 +128,10 @@ def to_fp8_codes(x: torch.Tensor, scale: float) -> torch.Tensor:
 
 
 def make_case_kv8(cfg: dict, seed: int, device="cpu", poison: bool = False, lens=None, k_scale: float = 1.0,
-                  v_scale: float = 1.0, table_width: int | None = None) -> dict:
+                  v_scale: float = 1.0, table_width: int | None = None, data_seed: int | None = None) -> dict:
     """As :func:`make_case` with the caches quantised to FP8 E4M3 codes: the values attended to are
     ``k_scale * decode(k_cache)`` and ``v_scale * decode(v_cache)``."""
-    c = make_case(cfg, seed, device, poison=poison, table_width=table_width, lens=lens)
+    c = make_case(cfg, seed, device, poison=poison, table_width=table_width, lens=lens, data_seed=data_seed)
     c["k_cache"] = to_fp8_codes(c["k_cache"], k_scale)
     c["v_cache"] = to_fp8_codes(c["v_cache"], v_scale)
     c["k_scale"], c["v_scale"] = float(k_scale), float(v_scale)

@@ -127,3 +127,45 @@ def test_layer_stack_configuration_sampled():
                                           cfg["Hq"], cfg["d"], pairs)
         sub = outs[l][torch.from_numpy(pairs[:, 0]).long().to(DEV), torch.from_numpy(pairs[:, 1]).long().to(DEV)]
         compare(sub, want, f"stack layer {l}")
+
+
+@pytest.mark.parametrize("cross", [0, 1])
+def test_layer_stack_can_be_captured_into_a_graph_and_replayed(cross):
+    """The whole stack (ticket fill, dense layers, attention, merges, optional side-stream touch) is recorded
+    by a stream capture; replays with new activations equal the eager result bit for bit."""
+    L, B, Hq, Hkv, d, bs, K, N = 2, 48, 8, 2, 128, 16, 1024, 1280
+    lens = np.random.default_rng(9).integers(1, 900, B).tolist()
+    cfg, layers, x, ws, y, outs = _stack(L, B, Hq, Hkv, d, bs, K, N, lens, 83)
+    wp = [kv.pack_weights(w, "operand") for w in ws]
+    c0 = layers[0]
+    ks, vs = [c["k_cache"] for c in layers], [c["v_cache"] for c in layers]
+
+    def enqueue(x_, y_, outs_):
+        kv.kv_decode_layerstack(x_, wp, y_, None, ks, vs, c0["block_tables"], c0["context_lens"], outs_, c0["scale"],
+                                c0["num_kv_heads"], c0["block_size"], 2, cross)
+
+    enqueue(x, y, outs)                         # eager warm-up: workspace, side stream and events exist afterwards
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue(x, y, outs)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        xn = synth.randn16((B, K), "bf16", 500 + rep, DEV)
+        yw = torch.empty_like(y)
+        want = [torch.empty_like(o) for o in outs]
+        enqueue(xn, yw, want)
+        torch.cuda.synchronize()
+        x.copy_(xn)
+        y.fill_(float("nan"))
+        for o in outs:
+            o.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), yw.view(torch.int16)), f"replay {rep}: dense layer"
+        for l in range(L):
+            assert torch.equal(outs[l].view(torch.int16), want[l].view(torch.int16)), f"replay {rep}: layer {l}"
+            assert torch.isfinite(outs[l].float()).all()

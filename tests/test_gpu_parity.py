@@ -280,3 +280,51 @@ def test_worker_timeline_accounts_for_every_tile():
     run_hip(case, 2)
     torch.cuda.synchronize()
     assert int(trace.abs().sum()) == 0
+
+
+def test_calls_can_be_captured_into_a_graph_and_replayed():
+    """kv_decode_attn and kv_decode_attn_kv8 enqueue only kernels on the caller's stream (no allocation, no
+    memset, no host synchronisation), so a stream capture records them; every replay, with new inputs copied
+    into the captured tensors and eager work in between, must equal the eager result bit for bit."""
+    cfg = dict(Hq=8, Hkv=2, d=128, bs=16, dtype="bf16")
+    lens = [900, 0, 17, 2500, 64, 1]
+    a = synth.make_case(cfg, 211, DEV, poison=True, lens=lens)
+    a8 = synth.make_case_kv8(cfg, 211, DEV, poison=True, lens=lens, k_scale=0.5, v_scale=2.0)
+    out, out8 = torch.empty_like(a["q"]), torch.empty_like(a["q"])
+
+    def enqueue():
+        kv.kv_decode_attn(a["q"], a["k_cache"], a["v_cache"], a["block_tables"], a["context_lens"], out, a["scale"],
+                          a["num_kv_heads"], a["block_size"], 2)
+        kv.kv_decode_attn_kv8(a8["q"], a8["k_cache"], a8["v_cache"], a8["block_tables"], a8["context_lens"], out8,
+                              a8["scale"], a8["k_scale"], a8["v_scale"], a8["num_kv_heads"], a8["block_size"], 1)
+
+    enqueue()                                   # eager warm-up: the workspace is allocated and registered here
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        # new values, same paging (and so the same poisoned slots)
+        b = synth.make_case(cfg, 211, DEV, poison=True, lens=lens, data_seed=300 + rep)
+        b8 = synth.make_case_kv8(cfg, 211, DEV, poison=True, lens=lens, k_scale=0.5, v_scale=2.0, data_seed=300 + rep)
+        for key in ("q", "k_cache", "v_cache"):
+            a[key].copy_(b[key])
+            a8[key].copy_(b8[key])
+        want, want8 = torch.empty_like(out), torch.empty_like(out8)
+        kv.kv_decode_attn(b["q"], b["k_cache"], b["v_cache"], a["block_tables"], a["context_lens"], want, a["scale"],
+                          a["num_kv_heads"], a["block_size"], 2)
+        kv.kv_decode_attn_kv8(b8["q"], b8["k_cache"], b8["v_cache"], a8["block_tables"], a8["context_lens"], want8,
+                              a8["scale"], a8["k_scale"], a8["v_scale"], a8["num_kv_heads"], a8["block_size"], 1)
+        torch.cuda.synchronize()
+        out.fill_(float("nan"))
+        out8.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want.view(torch.int16)), f"replay {rep}"
+        assert torch.equal(out8.view(torch.int16), want8.view(torch.int16)), f"replay {rep}, 8-bit cache"
+        assert torch.isfinite(out.float()).all() and torch.isfinite(out8.float()).all()
+    compare(out, run_oracle(a), "last replay")
