@@ -205,7 +205,6 @@ __device__ __forceinline__ u32x2 widen_fp8x4(uint32_t w) {
 
 constexpr int kAuxNonTemporal = 2;                   // cache-policy operand of global_load_lds: nt
 constexpr int kTileTokens = 16;
-constexpr int kMaxWorkers = 4096;
 
 // Per-head_dim geometry of a 16-token tile.
 template <int D>
@@ -249,9 +248,8 @@ __device__ __forceinline__ int wave_sum_i32(int v) {
     return v;
 }
 
-// Per-kv-head tile total of the batch, and (optionally) for a flat position `target` the
-// sequence that holds it: the last b whose first flat tile Hkv * cum[b] is <= target.
-struct ScanResult { int total; int b; int cum_b; };
+// scan_total: per-kv-head tile total of the batch.  scan_locate: for a flat position `target`, the sequence
+// that holds it, i.e. the last b whose first flat tile Hkv * cum[b] is <= target, and that cum[b].
 
 __device__ __forceinline__ int scan_total(const_i32_ptr cl, int B, int max_len, int lane) {
     int total = 0;
@@ -786,7 +784,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_touch_kernel(AttnParams p, int
 }
 
 int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* sink, hipStream_t stream) {
-    if (p.num_workers < 1 || p.num_workers > kMaxWorkers) return -1;
+    if (p.num_workers < 1 || p.num_workers > kMaxMfmaWorkers) return -1;
     const dim3 grid(p.num_workers), block(kWaveSize);
     if (d == 128) {
         if (bs == 16) hipLaunchKernelGGL((attn_touch_kernel<128, 16>), grid, block, 0, stream, p, tiles, sink);
@@ -800,7 +798,7 @@ int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* s
 
 // Returns 0 or -1 (no such instantiation).
 int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, bool kv8, hipStream_t stream) {
-    if (p.num_workers < 1 || p.num_workers > kMaxWorkers) return -1;
+    if (p.num_workers < 1 || p.num_workers > kMaxMfmaWorkers) return -1;
     if (d != 64 && d != 128) return -1;
     if (bs != 16 && bs != 32) return -1;
     if (kv8) return elem == (int)Elem::F16 ? launch_shape<Elem::F16, true>(p, d, bs, stream) : launch_shape<Elem::BF16, true>(p, d, bs, stream);

@@ -126,3 +126,26 @@ def test_wrong_cache_type_and_scales_are_rejected():
             kv.kv_decode_attn_kv8(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], out,
                                   c["scale"], ks, vs, 2, 16, 1)
         assert e.value.status == 1
+
+
+def test_strided_cache_views_and_a_side_stream():
+    """Caches that are slices of a larger pool (block and head strides larger than dense, still multiples of 16
+    bytes), q and out as column slices, launched on a non-default stream."""
+    cfg = dict(Hq=8, Hkv=2, d=128, bs=16, dtype="f16")
+    c = synth.make_case_kv8(cfg, 61, DEV, poison=True, lens=[500, 31, 1200], v_scale=0.25)
+    nblk = c["k_cache"].shape[0]
+    big_k = torch.full((nblk, 3, 16, 128), 0x7f, dtype=torch.uint8, device=DEV)     # NaN codes around the real heads
+    big_v = torch.full((nblk, 3, 16, 128), 0xff, dtype=torch.uint8, device=DEV)
+    big_k[:, :2] = c["k_cache"]
+    big_v[:, :2] = c["v_cache"]
+    qbig = torch.zeros((3, 8, 256), dtype=torch.float16, device=DEV)
+    qbig[:, :, 64:192] = c["q"]
+    obig = torch.full((3, 8, 256), float("nan"), dtype=torch.float16, device=DEV)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        kv.kv_decode_attn_kv8(qbig[:, :, 64:192], big_k[:, :2], big_v[:, :2], c["block_tables"], c["context_lens"],
+                              obig[:, :, 64:192], c["scale"], c["k_scale"], c["v_scale"], 2, 16, 2)
+    s.synchronize()
+    assert torch.isnan(obig[:, :, :64]).all() and torch.isnan(obig[:, :, 192:]).all()
+    compare(obig[:, :, 64:192], run_oracle(c), "strided views")
