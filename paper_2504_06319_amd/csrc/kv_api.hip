@@ -29,19 +29,21 @@ size_t g_ws_bytes = 0;
 void* g_trace_ptr = nullptr;         // optional per-worker timestamps (under g_ws_mutex)
 size_t g_trace_bytes = 0;
 std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
-std::atomic<int> g_num_cus{0};       // compute units of the device, read once
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_num_cus[kMaxDevices];   // compute units per device ordinal, read once each (0 = not read yet)
 
 constexpr int kLdsBytesPerCU = 160 * 1024;
 constexpr int kMaxWavesPerCU = 16;
 
-int num_cus() {
-    int n = g_num_cus.load();
-    if (n > 0) return n;
+int num_cus() {     // of the current device
     int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    int n = g_num_cus[dev].load();
+    if (n > 0) return n;
     hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return -1;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return -1;
     n = prop.multiProcessorCount;
-    g_num_cus.store(n);
+    g_num_cus[dev].store(n);
     return n;
 }
 
@@ -51,9 +53,9 @@ int num_cus() {
 // keeps max(1, distance) tile pairs of 8 KB (head_dim 128) or 4 KB (head_dim 64) in flight, so deep look-ahead
 // wants few waves and no look-ahead wants many; head_dim 64 needs at least four waves to keep up with the
 // arithmetic of its smaller tiles.  An 8-bit cache halves the bytes of a tile and adds the widening to the
-// arithmetic, so it wants more waves for both reasons (measured: 12 waves without look-ahead and 6 with at head_dim 128,
-// 16 and 12 at head_dim 64; 10 or 13 waves, uneven over the four SIMDs, are 25 % slower, so its count is kept even).  Always
-// capped by the LDS the rings need.
+// arithmetic, so it wants more waves for both reasons (measured: 12 waves without look-ahead and 6 with at
+// head_dim 128, 16 and 12 at head_dim 64; 10 or 13 waves, uneven over the four SIMDs, are 25 % slower, so its
+// count is kept even).  Always capped by the LDS the rings need.
 int waves_per_cu(int prefetch_distance, int d, bool kv8) {
     const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance, d, kv8);
     int w = g_waves_per_cu.load();
