@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import oracle
 import paper_2504_06319_amd as kv
 from paper_2504_06319_amd import synth
 from kvcheck import check_case, compare, host_bits, run_hip, run_oracle
@@ -328,3 +329,50 @@ def test_calls_can_be_captured_into_a_graph_and_replayed():
         assert torch.equal(out8.view(torch.int16), want8.view(torch.int16)), f"replay {rep}, 8-bit cache"
         assert torch.isfinite(out.float()).all() and torch.isfinite(out8.float()).all()
     compare(out, run_oracle(a), "last replay")
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_randomised_shapes_lengths_and_launch_settings(seed):
+    """Seeded random draws over everything a caller can vary: batch, group size, kv heads, head_dim, block size,
+    type, length mix (including empty and one-token sequences), table width, prefetch distance, waves per compute
+    unit, and the 16-bit or 8-bit cache."""
+    rng = np.random.default_rng(1000 + seed)
+    G = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16]))
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    d = int(rng.choice([64, 128]))
+    bs = int(rng.choice([16, 32]))
+    dtype = str(rng.choice(["bf16", "f16"]))
+    B = int(rng.integers(1, 40))
+    kind = rng.integers(0, 3)
+    if kind == 0:
+        lens = rng.integers(0, 60, B)                       # tiny contexts, many empty
+    elif kind == 1:
+        lens = rng.integers(1, 3000, B)
+    else:
+        lens = np.where(rng.random(B) < 0.2, rng.integers(3000, 20000, B), rng.integers(0, 200, B))   # a few long ones
+    lens = lens.astype(np.int64).tolist()
+    pd = int(rng.integers(0, kv.KV_MAX_PREFETCH_DISTANCE + 1))
+    waves = int(rng.choice([0, 1, 2, 3, 5, 6, 8, 11, 16]))
+    width = (max(lens) + bs - 1) // bs + int(rng.integers(0, 5))
+    cfg = dict(Hq=G * Hkv, Hkv=Hkv, d=d, bs=bs, dtype=dtype)
+    kv8 = bool(rng.integers(0, 2))
+    what = f"seed {seed}: B {B} G {G} Hkv {Hkv} d {d} bs {bs} {dtype} pd {pd} waves {waves} kv8 {kv8} kind {kind}"
+    print(what, flush=True)
+    kv.kv_decode_set_waves_per_cu(waves)
+    try:
+        if kv8:
+            c = synth.make_case_kv8(cfg, 2000 + seed, DEV, poison=True, lens=lens, k_scale=0.75, v_scale=1.5,
+                                    table_width=max(width, 1))
+            out = torch.full_like(c["q"], float("nan"))
+            kv.kv_decode_attn_kv8(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], out,
+                                  c["scale"], c["k_scale"], c["v_scale"], Hkv, bs, pd)
+            torch.cuda.synchronize()
+            want = oracle.paged_attention_kv8(oracle.bits_of(c["q"]), c["k_cache"].cpu().numpy(), c["v_cache"].cpu().numpy(),
+                                              c["block_tables"].cpu().numpy(), c["context_lens"].cpu().numpy(), c["scale"],
+                                              dtype, c["k_scale"], c["v_scale"])
+            compare(out, want, what)
+        else:
+            c = synth.make_case(cfg, 2000 + seed, DEV, poison=True, lens=lens, table_width=max(width, 1))
+            compare(run_hip(c, pd), run_oracle(c), what)
+    finally:
+        kv.kv_decode_set_waves_per_cu(0)
