@@ -105,13 +105,15 @@ def worker_timeline(kv, torch, cases, pd, launches=8):
         kv.kv_decode_set_worker_trace(None)
     t = trace.cpu().numpy()
     t = t[t[:, 3] > 0]                         # workers that had a range
+    xcd, t[:, 3] = t[:, 3] >> 32, t[:, 3] & 0xffffffff
     t0 = t[:, 0].min()
     us = lambda col: (t[:, col] - t0) / 100.0
     pct = lambda a: {f"p{q}": round(float(np.percentile(a, q)), 2) for q in (0, 10, 50, 90, 100)}
     return {"workers": int(len(t)), "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd, cfg_d),
             "tiles_per_worker": [int(t[:, 3].min()), int(t[:, 3].max())],
             "entry_us": pct(us(0)), "range_located_us": pct(us(1)), "exit_us": pct(us(2)),
-            "busy_us": pct((t[:, 2] - t[:, 1]) / 100.0)}
+            "busy_us": pct((t[:, 2] - t[:, 1]) / 100.0),
+            "mean_exit_us_by_xcd": {int(x): round(float(us(2)[xcd == x].mean()), 2) for x in np.unique(xcd)}}
 
 
 def heatmap(kv, torch, synth, dev, pd_on, steps=20, warmup=4):

@@ -157,6 +157,15 @@ int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
 int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
 
 /*
+ * Skew of the workers' shares of the tile space between the even and the odd XCD of every XCD
+ * pair, in 1/1024: worker w gets 1024 + skew parts when w is even and 1024 - skew when it is odd
+ * (workgroups go to the XCDs round-robin; under load the odd XCD of a pair delivers about 3 % less
+ * bandwidth).  0 gives equal shares; 0 .. 256; default 20.  Results depend on it only through
+ * where units are cut (rounding of the merge), like on the worker count.
+ */
+int kv_decode_set_xcd_skew(int per_1024);
+
+/*
  * Timing of the main attention kernel with HIP events on the call's own stream (the paper
  * reports the attention kernel's duration, Table 2).  kv_profile_enable(n, every) creates
  * events for n samples (host-side allocation, not on the timed path; n = 0 frees them); while
@@ -174,8 +183,9 @@ int kv_profile_read(double* main_ms_sum, int* calls);
  * paper's Table 1 asks that of its baseline kernel with a profiler; this is the kernel's own
  * account).  While device memory is registered here, every persistent worker w of a launch with
  * at most bytes / 32 workers writes four 64-bit words at dev_ptr + 32 w: the constant 100 MHz
- * clock at entry, after it has located its range, at exit, and the number of tiles it
- * processed.  NULL/0 unregisters.  The caller owns the memory and reads it after synchronising;
+ * clock at entry, after it has located its range, at exit, and a word whose low 32 bits are the
+ * number of tiles it processed and whose high 32 bits are the XCD (XCC_ID) it ran on.
+ * NULL/0 unregisters.  The caller owns the memory and reads it after synchronising;
  * launches with more workers than fit leave it untouched.  Costs two clock reads per worker.
  */
 int kv_decode_set_worker_trace(void* dev_ptr, size_t bytes);

@@ -41,7 +41,7 @@ class KVTensor(ctypes.Structure):
 
 EXPORTS = [
     "kv_decode_attn", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
-    "kv_decode_set_workspace", "kv_decode_set_worker_trace",
+    "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_profile_enable", "kv_profile_read",
 ]
@@ -205,6 +205,10 @@ def kv_decode_attn_kv8(q, k_cache, v_cache, block_tables, context_lens, out, sca
     _check(lib.kv_decode_attn_kv8(*[ctypes.byref(d) for d in descs], float(scale), float(k_scale), float(v_scale), int(num_kv_heads), int(block_size), int(prefetch_distance),
                                   ctypes.c_void_p(_stream_handle(stream))))
     return out
+
+
+def kv_decode_set_xcd_skew(per_1024: int):
+    _check(load_library().kv_decode_set_xcd_skew(int(per_1024)))
 
 
 def kv_decode_get_waves_per_cu_kv8(prefetch_distance: int, head_dim: int = 128) -> int:

@@ -286,9 +286,27 @@ __device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len
     cum_out = found_cum;
 }
 
-__device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_workers) {
-    return (int64_t)worker * T / num_workers;
+// Range boundaries of the flat tile space.  Worker w's share is proportional to 1024 + skew for even w and
+// 1024 - skew for odd w: workgroups go to the eight XCDs round-robin, and under load the odd XCD of every XCD
+// pair delivers 3-4 % less bandwidth than the even one (per-worker exit times, grouped by XCC_ID), so
+// equal shares would leave the even XCDs idle at the end.  The cumulative weight of workers [0, w) is
+// 1024 w + skew (w & 1).  Ranges of fewer than 64 tiles are not skewed.
+__device__ __forceinline__ int effective_skew(int64_t T, int num_workers, int skew) {
+    return T >= 64 * (int64_t)num_workers ? skew : 0;
 }
+__device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_workers, int skew) {
+    const int64_t total = 1024 * (int64_t)num_workers + skew * (num_workers & 1);
+    return T * (1024 * (int64_t)worker + skew * (worker & 1)) / total;
+}
+// Last worker whose range starts at or before flat tile x (0 <= x < T).
+__device__ __forceinline__ int range_owner(int64_t x, int64_t T, int num_workers, int skew) {
+    int w = (int)(x * num_workers / T);
+    while (w > 0 && range_start(w, T, num_workers, skew) > x) --w;
+    while (w + 1 < num_workers && range_start(w + 1, T, num_workers, skew) <= x) ++w;
+    return w;
+}
+// XCC_ID field (bits 3:0) of hardware register 20: the XCD this wave runs on.
+__device__ __forceinline__ int xcc_id() { return (int)__builtin_amdgcn_s_getreg((3 << 11) | 20); }
 
 // KV8: the caches hold FP8 E4M3 codes (one byte per element); q and out are of type E.
 template <Elem E, int D, int BS, int PD, bool KV8>
@@ -328,8 +346,9 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     // worker's range is non-empty
     const int nw = T < p.num_workers ? (int)T : p.num_workers;
     if (worker >= nw) return;
-    const int64_t r0 = range_start(worker, T, nw);
-    const int64_t r1 = range_start(worker + 1, T, nw);
+    const int skew = effective_skew(T, nw, p.xcd_skew);
+    const int64_t r0 = range_start(worker, T, nw, skew);
+    const int64_t r1 = range_start(worker + 1, T, nw, skew);
     Cursor ca;
     {
         int b0, cum0;
@@ -606,7 +625,8 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     }
     if (traced && lane == 0) {
         unsigned long long* t = p.worker_trace + (int64_t)worker * 4;
-        t[0] = t_entry; t[1] = t_scan; t[2] = wall_clock64(); t[3] = (unsigned long long)(r1 - r0);
+        t[0] = t_entry; t[1] = t_scan; t[2] = wall_clock64();
+        t[3] = (unsigned long long)(r1 - r0) | ((unsigned long long)xcc_id() << 32);
     }
 }
 
@@ -643,11 +663,12 @@ __global__ __launch_bounds__(D) void attn_finalize_kernel(AttnParams p, int bs) 
     const int64_t T = (int64_t)total * Hkv;
     const int nw = T < p.num_workers ? (int)T : p.num_workers;
     const int64_t a = (int64_t)Hkv * cum + (int64_t)kvh * nt, end = a + nt;     // the unit's flat tile range
-    const int w0 = (int)(((a + 1) * nw - 1) / T);   // last worker whose range starts at or before a
-    const int w1 = (int)((end * nw - 1) / T);       // last worker whose range starts before end
+    const int skew = effective_skew(T, nw, p.xcd_skew);
+    const int w0 = range_owner(a, T, nw, skew);         // last worker whose range starts at or before a
+    const int w1 = range_owner(end - 1, T, nw, skew);   // last worker whose range starts before end
     if (w0 == w1) return;                           // one worker covered the unit and wrote the rows itself
     const int np = w1 - w0 + 1;
-    const int slot_first = range_start(w0, T, nw) < a ? 1 : 0;
+    const int slot_first = range_start(w0, T, nw, skew) < a ? 1 : 0;
     const float* first_row = p.partials + ((int64_t)(w0 * 2 + slot_first) * G + g) * PS;
     const float* later_rows = p.partials + ((int64_t)(w0 * 2) * G + g) * PS;     // + i * 2 * G * PS for piece i >= 1
 
@@ -752,7 +773,8 @@ __global__ __launch_bounds__(kWaveSize) void attn_touch_kernel(AttnParams p, int
     const int64_t T = (int64_t)total * Hkv;
     const int nw = T < p.num_workers ? (int)T : p.num_workers;
     if (worker >= nw) return;
-    const int64_t r0 = range_start(worker, T, nw), r1 = range_start(worker + 1, T, nw);
+    const int skew = effective_skew(T, nw, p.xcd_skew);
+    const int64_t r0 = range_start(worker, T, nw, skew), r1 = range_start(worker + 1, T, nw, skew);
     int b0, cum0;
     scan_locate(cl, p.B, max_len, lane, Hkv, r0, b0, cum0);
     int b = b0, n = clamp_len(cl[b0], max_len), ntiles = tiles_of(n);

@@ -29,6 +29,7 @@ size_t g_ws_bytes = 0;
 void* g_trace_ptr = nullptr;         // optional per-worker timestamps (under g_ws_mutex)
 size_t g_trace_bytes = 0;
 std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
+std::atomic<int> g_xcd_skew{20};     // per 1024: even workers get 1024 + 20 parts of the tile space, odd ones 1024 - 20
 constexpr int kMaxDevices = 64;
 std::atomic<int> g_num_cus[kMaxDevices];   // compute units per device ordinal, read once each (0 = not read yet)
 
@@ -175,6 +176,7 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
     const int nw = cus * waves_per_cu(prefetch_distance, (int)d, kv8);
     p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
+    p.xcd_skew = g_xcd_skew.load();
     const size_t need = kvp::kGemmTicketBytes + kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     if (!g_ws_ptr || g_ws_bytes < need)
@@ -392,6 +394,13 @@ int kv_decode_set_waves_per_cu(int waves) {
     if (waves < 0 || waves > kMaxWavesPerCU)
         return fail(KV_ERR_INVALID, "kv_decode_set_waves_per_cu: %d outside 0..%d", waves, kMaxWavesPerCU);
     g_waves_per_cu.store(waves);
+    return KV_OK;
+}
+
+int kv_decode_set_xcd_skew(int per_1024) {
+    if (per_1024 < 0 || per_1024 > 256)
+        return fail(KV_ERR_INVALID, "kv_decode_set_xcd_skew: %d outside 0..256", per_1024);
+    g_xcd_skew.store(per_1024);
     return KV_OK;
 }
 

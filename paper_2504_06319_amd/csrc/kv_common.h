@@ -30,6 +30,7 @@ struct AttnParams {
     int32_t NBLK;             // physical blocks in the cache
     int32_t prefetch_distance;
     int32_t num_workers;      // persistent waves (workers) of the launch
+    int32_t xcd_skew;         // per-1024 skew of the range sizes between even and odd workers (XCDs)
     float scale_log2e;        // scale * log2(e) (* k_scale for an 8-bit cache): logits live in the base-2 domain
     float out_scale;          // multiplies every output row: 1, or v_scale for an 8-bit cache
 };

@@ -96,6 +96,30 @@ def test_other_worker_counts_cut_units_differently(waves, pd, d):
         kv.kv_decode_set_waves_per_cu(0)
 
 
+@pytest.mark.parametrize("skew", [0, 20, 256])
+def test_skewed_shares_of_even_and_odd_workers(skew):
+    """Even workers take 1024 + skew parts of the tile space and odd ones 1024 - skew (the two XCDs of a pair
+    differ in delivered bandwidth); every skew cuts the units elsewhere and must give the same result."""
+    lens = [60000, 0, 33, 45000, 17, 30000, 1, 7000]
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 59, DEV, poison=True, lens=lens)
+    trace = torch.zeros((4096, 4), dtype=torch.int64, device=DEV)
+    kv.kv_decode_set_waves_per_cu(1)
+    kv.kv_decode_set_xcd_skew(skew)
+    kv.kv_decode_set_worker_trace(trace)
+    try:
+        got = run_hip(c, 2)
+    finally:
+        kv.kv_decode_set_worker_trace(None)
+        kv.kv_decode_set_xcd_skew(20)
+        kv.kv_decode_set_waves_per_cu(0)
+    compare(got, run_oracle(c), f"skew={skew}")
+    tiles = trace.cpu().numpy()[:256, 3] & 0xffffffff
+    T = sum((n + 15) // 16 for n in lens) * 2
+    assert T >= 64 * 256 and tiles.sum() == T
+    share = T / 256 / 1024
+    assert abs(tiles[0::2].mean() - share * (1024 + skew)) < 1 and abs(tiles[1::2].mean() - share * (1024 - skew)) < 1
+
+
 def test_single_unit_spanning_every_worker():
     c = synth.make_case(_cfg(4, 1, 128, 32, "f16"), 47, DEV, poison=True, lens=[70001])
     check_case(c, 2, "one unit")
@@ -271,6 +295,8 @@ def test_worker_timeline_accounts_for_every_tile():
         kv.kv_decode_set_worker_trace(None)
     t = trace.cpu().numpy()
     active = t[t[:, 3] > 0]
+    xcd, active[:, 3] = active[:, 3] >> 32, active[:, 3] & 0xffffffff
+    assert ((xcd >= 0) & (xcd < 8)).all()
     tiles = sum((n + 15) // 16 for n in lens) * cfg["Hkv"]
     assert active[:, 3].sum() == tiles
     assert len(active) == min(tiles, 256 * kv.kv_decode_get_waves_per_cu(2, 128))
