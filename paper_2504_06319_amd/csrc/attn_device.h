@@ -1,0 +1,181 @@
+// Device-side pieces shared by the attention kernels: operand types and MFMA wrappers, lane-swap reductions,
+// counted waits, the flat tile space (lengths scan, worker ranges, cursor) and the FP8 widening.
+#pragma once
+#include "kv_common.h"
+
+namespace kvp {
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define KVP_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+#define KVP_GLOBAL(p) ((const __attribute__((address_space(1))) void*)(p))
+
+template <Elem E>
+__device__ __forceinline__ float4v mfma_k32(u32x4 a, u32x4 b, float4v c) {
+    if constexpr (E == Elem::BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+}
+
+template <Elem E>
+__device__ __forceinline__ float4v mfma_k16(u32x2 a, u32x2 b, float4v c) {
+    if constexpr (E == Elem::BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4v, a), __builtin_bit_cast(short4v, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, a), __builtin_bit_cast(half4, b), c, 0, 0, 0);
+}
+
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+// Two floats -> two 16-bit patterns in one dword (lo in bits 15:0), round to nearest even; one packed convert.
+template <Elem E>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    const float2v f = {lo, hi};
+    if constexpr (E == Elem::BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, half2v));
+}
+
+// The values of the lanes 16 and 32 away (lane ^ 16, lane ^ 32), by the lane-swap instructions: a register-file
+// operation, where a shuffle would be a round trip through the LDS crossbar on the critical path of every tile.
+// v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of its second,
+// v_permlane32_swap the upper half of the first with the lower half of the second; fed the same value twice, the
+// two results hold, for every lane, its own value and the partner's, in some order.
+struct LanePair { float a, b; };
+__device__ __forceinline__ LanePair swap16(float v) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, v);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const uint32_t r0 = r[0], r1 = r[1];        // copies: a bit_cast applied to a vector element reads element 0
+    return {__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+__device__ __forceinline__ LanePair swap32(float v) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const uint32_t r0 = r[0], r1 = r[1];        // copies: a bit_cast applied to a vector element reads element 0
+    return {__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+// max / sum over the four lanes {lr, lr + 16, lr + 32, lr + 48}
+__device__ __forceinline__ float group_max(float v) {
+    LanePair p = swap16(v);
+    v = fmaxf(p.a, p.b);
+    p = swap32(v);
+    return fmaxf(p.a, p.b);
+}
+__device__ __forceinline__ float group_sum(float v) {
+    LanePair p = swap16(v);
+    v = p.a + p.b;
+    p = swap32(v);
+    return p.a + p.b;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    // gfx9 encoding of s_waitcnt: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt and lgkmcnt left at max
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | 0x0f70);
+}
+
+// four FP8 E4M3 codes of a dword -> four 16-bit values of type E in two dwords (exact: both 16-bit types hold every
+// E4M3 value)
+template <Elem E>
+__device__ __forceinline__ u32x2 widen_fp8x4(uint32_t w) {
+    if constexpr (E == Elem::BF16) {
+        return u32x2{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false)),
+                     __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true))};
+    } else {
+        return u32x2{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false)),
+                     __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true))};
+    }
+}
+
+constexpr int kAuxNonTemporal = 2;                   // cache-policy operand of global_load_lds: nt
+
+// Position of a worker inside the flat tile space; every field is wave-uniform.
+struct Cursor {
+    int b;        // sequence
+    int kvh;      // kv head
+    int j;        // tile index inside the sequence
+    int ntiles;   // tiles of sequence b
+    int n;        // clamped context length of sequence b
+};
+
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;   // uniform loads become scalar loads
+
+__device__ __forceinline__ int clamp_len(int n, int max_len) { return min(max(n, 0), max_len); }
+// tiles of 2^shift tokens that n tokens occupy (16-token tiles for 16-bit caches, 32-token tiles for 8-bit ones)
+__device__ __forceinline__ int tiles_of(int n, int shift) { return (n + (1 << shift) - 1) >> shift; }
+
+__device__ __forceinline__ int wave_sum_i32(int v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// scan_total: per-kv-head tile total of the batch.  scan_locate: for a flat position `target`, the sequence
+// that holds it, i.e. the last b whose first flat tile Hkv * cum[b] is <= target, and that cum[b].
+
+__device__ __forceinline__ int scan_total(const_i32_ptr cl, int B, int max_len, int lane, int shift) {
+    int total = 0;
+    for (int base = 0; base < B; base += kWaveSize) {
+        const int idx = base + lane;
+        const int t = idx < B ? tiles_of(clamp_len(cl[idx], max_len), shift) : 0;
+        total += wave_sum_i32(t);
+    }
+    return __builtin_amdgcn_readfirstlane(total);   // every lane holds the sum: make it a scalar for the compiler too
+}
+
+__device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len, int lane, int shift, int Hkv,
+                                            int64_t target, int& b_out, int& cum_out) {
+    int cum = 0, found_b = 0, found_cum = 0;
+    for (int base = 0; base < B; base += kWaveSize) {
+        const int idx = base + lane;
+        const int t = idx < B ? tiles_of(clamp_len(cl[idx], max_len), shift) : 0;
+        int incl = t;
+#pragma unroll
+        for (int off = 1; off < kWaveSize; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        const int excl = cum + incl - t;
+        const bool pred = idx < B && (int64_t)Hkv * excl <= target;
+        const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(pred));
+        if (cnt == 0) break;                       // the predicate is monotone: nothing further matches
+        found_b = base + cnt - 1;
+        found_cum = __builtin_amdgcn_readlane(excl, cnt - 1);
+        cum += __builtin_amdgcn_readlane(incl, kWaveSize - 1);
+        if (cnt < kWaveSize) break;
+    }
+    b_out = found_b;
+    cum_out = found_cum;
+}
+
+// Range boundaries of the flat tile space.  Worker w's share is proportional to 1024 + skew for even w and
+// 1024 - skew for odd w: workgroups go to the eight XCDs round-robin, and under load the odd XCD of every XCD
+// pair delivers 3-4 % less bandwidth than the even one (per-worker exit times, grouped by XCC_ID), so
+// equal shares would leave the even XCDs idle at the end.  The cumulative weight of workers [0, w) is
+// 1024 w + skew (w & 1).  Ranges of fewer than 64 tiles are not skewed.
+__device__ __forceinline__ int effective_skew(int64_t T, int num_workers, int skew) {
+    return T >= 64 * (int64_t)num_workers ? skew : 0;
+}
+__device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_workers, int skew) {
+    const int64_t total = 1024 * (int64_t)num_workers + skew * (num_workers & 1);
+    return T * (1024 * (int64_t)worker + skew * (worker & 1)) / total;
+}
+// Last worker whose range starts at or before flat tile x (0 <= x < T).
+__device__ __forceinline__ int range_owner(int64_t x, int64_t T, int num_workers, int skew) {
+    int w = (int)(x * num_workers / T);
+    while (w > 0 && range_start(w, T, num_workers, skew) > x) --w;
+    while (w + 1 < num_workers && range_start(w + 1, T, num_workers, skew) <= x) ++w;
+    return w;
+}
+// XCC_ID field (bits 3:0) of hardware register 20: the XCD this wave runs on.
+__device__ __forceinline__ int xcc_id() { return (int)__builtin_amdgcn_s_getreg((3 << 11) | 20); }
+
+}  // namespace kvp

@@ -36,94 +36,12 @@
 // avoided by permuting which 16-byte chunk of a row each lane fetches: with C = d/8 chunks per
 // row and s = row / (16/C), K rows are stored with chunk index XOR (s mod C), V rows with
 // chunk index XOR (2*(s mod C/2) XOR (s mod 2)) (d = 128: XOR row, and XOR 2*(row mod 8) XOR (row mod 2)).
-//
-// 8-bit cache (KV8): the ring holds the raw FP8 E4M3 tiles (half the bytes).  The K operand of an
-// MFMA is eight codes per lane read straight from the raw tile (chunk-swizzled on the fetch side for
-// that read) and widened to the query's 16-bit type in registers; the V tile is widened into one
-// more LDS tile laid out exactly as above, because the transpose read works on 16-bit elements.
-// Everything downstream is shared with the 16-bit path.
-#include "kv_common.h"
+#include "attn_device.h"
 
 #include <type_traits>
 
 namespace kvp {
 
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-typedef float float4v __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-#define KVP_LDS(p) ((__attribute__((address_space(3))) void*)(p))
-#define KVP_GLOBAL(p) ((const __attribute__((address_space(1))) void*)(p))
-
-template <Elem E>
-__device__ __forceinline__ float4v mfma_k32(u32x4 a, u32x4 b, float4v c) {
-    if constexpr (E == Elem::BF16)
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
-}
-
-template <Elem E>
-__device__ __forceinline__ float4v mfma_k16(u32x2 a, u32x2 b, float4v c) {
-    if constexpr (E == Elem::BF16)
-        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4v, a), __builtin_bit_cast(short4v, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, a), __builtin_bit_cast(half4, b), c, 0, 0, 0);
-}
-
-typedef float float2v __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-
-// Two floats -> two 16-bit patterns in one dword (lo in bits 15:0), round to nearest even; one packed convert.
-template <Elem E>
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    const float2v f = {lo, hi};
-    if constexpr (E == Elem::BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
-    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, half2v));
-}
-
-// The values of the lanes 16 and 32 away (lane ^ 16, lane ^ 32), by the lane-swap instructions: a register-file
-// operation, where a shuffle would be a round trip through the LDS crossbar on the critical path of every tile.
-// v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of its second,
-// v_permlane32_swap the upper half of the first with the lower half of the second; fed the same value twice, the
-// two results hold, for every lane, its own value and the partner's, in some order.
-struct LanePair { float a, b; };
-__device__ __forceinline__ LanePair swap16(float v) {
-    const uint32_t u = __builtin_bit_cast(uint32_t, v);
-    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    const uint32_t r0 = r[0], r1 = r[1];        // copies: a bit_cast applied to a vector element reads element 0
-    return {__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
-}
-__device__ __forceinline__ LanePair swap32(float v) {
-    const uint32_t u = __builtin_bit_cast(uint32_t, v);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    const uint32_t r0 = r[0], r1 = r[1];        // copies: a bit_cast applied to a vector element reads element 0
-    return {__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
-}
-// max / sum over the four lanes {lr, lr + 16, lr + 32, lr + 48}
-__device__ __forceinline__ float group_max(float v) {
-    LanePair p = swap16(v);
-    v = fmaxf(p.a, p.b);
-    p = swap32(v);
-    return fmaxf(p.a, p.b);
-}
-__device__ __forceinline__ float group_sum(float v) {
-    LanePair p = swap16(v);
-    v = p.a + p.b;
-    p = swap32(v);
-    return p.a + p.b;
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    // gfx9 encoding of s_waitcnt: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt and lgkmcnt left at max
-    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | 0x0f70);
-}
 
 // LDS reads of the ring are written as inline assembly on purpose.  The compiler knows
 // that global_load_lds writes LDS and, unable to tell ring stages apart, would put a
@@ -172,39 +90,9 @@ __device__ __forceinline__ void lds_wait_v(u32x2 (&r)[8]) {
                  : "memory");
 }
 
-// ---- 8-bit KV cache: raw FP8 E4M3 tiles land in the ring as they are in HBM and are widened to the query's
-// 16-bit type into an LDS image of the tile pair that the operand reads below take exactly as they take a 16-bit
-// stage.  These LDS accesses are inline assembly for the same reason as the operand reads.
-__device__ __forceinline__ void lds_read_raw(u32x4& r, uint32_t a) {
-    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(a) : "memory");
-}
-__device__ __forceinline__ void lds_read_raw64(u32x2& r, uint32_t a) {
-    asm volatile("ds_read_b64 %0, %1" : "=v"(r) : "v"(a) : "memory");
-}
-__device__ __forceinline__ void lds_wait_raw(u32x2 (&k)[4], u32x4 (&v)[2]) {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(k[0]), "+v"(k[1]), "+v"(k[2]), "+v"(k[3]), "+v"(v[0]), "+v"(v[1]) : : "memory");
-}
-__device__ __forceinline__ void lds_wait_raw(u32x2 (&k)[2], u32x4 (&v)[1]) {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(k[0]), "+v"(k[1]), "+v"(v[0]) : : "memory");
-}
-__device__ __forceinline__ void lds_write_b128(uint32_t a, u32x4 v) {
-    asm volatile("ds_write_b128 %0, %1" : : "v"(a), "v"(v) : "memory");
-}
-// four FP8 E4M3 codes of a dword -> four 16-bit values of type E in two dwords (exact: both 16-bit types hold every
-// E4M3 value)
-template <Elem E>
-__device__ __forceinline__ u32x2 widen_fp8x4(uint32_t w) {
-    if constexpr (E == Elem::BF16) {
-        return u32x2{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false)),
-                     __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true))};
-    } else {
-        return u32x2{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false)),
-                     __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true))};
-    }
-}
 
-constexpr int kAuxNonTemporal = 2;                   // cache-policy operand of global_load_lds: nt
 constexpr int kTileTokens = 16;
+constexpr int kTileShift = 4;
 
 // Per-head_dim geometry of a 16-token tile.
 template <int D>
@@ -220,112 +108,20 @@ struct Geo {
     static constexpr int kColBlocks = D / 16;                      // 16-column blocks of the output
     static constexpr int kPartialStride = D + 4;                   // floats per partial row: acc, max, sum, 2 pad (16-byte rows)
     __host__ __device__ static constexpr int swz_k(int row) { return (row / kSwzShift) % kChunks; }
-    // V swizzle of the 16-byte chunk index: the even part moves the 32-byte block a transpose read takes, the low
-    // bit swaps the halves of that block on every other swizzle row so that the widening writes of an 8-bit cache
-    // (two adjacent chunks per lane) spread over all banks as well
-    __host__ __device__ static constexpr int swz_v(int row) {
-        return 2 * ((row / kSwzShift) % (kChunks / 2)) ^ ((row / kSwzShift) & 1);
-    }
+    // V swizzle of the 16-byte chunk index: even, so that it moves the 32-byte block a transpose read takes
+    __host__ __device__ static constexpr int swz_v(int row) { return 2 * ((row / kSwzShift) % (kChunks / 2)); }
 };
 
-// Position of a worker inside the flat tile space; every field is wave-uniform.
-struct Cursor {
-    int b;        // sequence
-    int kvh;      // kv head
-    int j;        // tile index inside the sequence
-    int ntiles;   // tiles of sequence b
-    int n;        // clamped context length of sequence b
-};
 
-typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;   // uniform loads become scalar loads
-
-__device__ __forceinline__ int clamp_len(int n, int max_len) { return min(max(n, 0), max_len); }
-__device__ __forceinline__ int tiles_of(int n) { return (n + kTileTokens - 1) / kTileTokens; }
-
-__device__ __forceinline__ int wave_sum_i32(int v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
-}
-
-// scan_total: per-kv-head tile total of the batch.  scan_locate: for a flat position `target`, the sequence
-// that holds it, i.e. the last b whose first flat tile Hkv * cum[b] is <= target, and that cum[b].
-
-__device__ __forceinline__ int scan_total(const_i32_ptr cl, int B, int max_len, int lane) {
-    int total = 0;
-    for (int base = 0; base < B; base += kWaveSize) {
-        const int idx = base + lane;
-        const int t = idx < B ? tiles_of(clamp_len(cl[idx], max_len)) : 0;
-        total += wave_sum_i32(t);
-    }
-    return __builtin_amdgcn_readfirstlane(total);   // every lane holds the sum: make it a scalar for the compiler too
-}
-
-__device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len, int lane, int Hkv,
-                                            int64_t target, int& b_out, int& cum_out) {
-    int cum = 0, found_b = 0, found_cum = 0;
-    for (int base = 0; base < B; base += kWaveSize) {
-        const int idx = base + lane;
-        const int t = idx < B ? tiles_of(clamp_len(cl[idx], max_len)) : 0;
-        int incl = t;
-#pragma unroll
-        for (int off = 1; off < kWaveSize; off <<= 1) {
-            const int up = __shfl_up(incl, off);
-            if (lane >= off) incl += up;
-        }
-        const int excl = cum + incl - t;
-        const bool pred = idx < B && (int64_t)Hkv * excl <= target;
-        const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(pred));
-        if (cnt == 0) break;                       // the predicate is monotone: nothing further matches
-        found_b = base + cnt - 1;
-        found_cum = __builtin_amdgcn_readlane(excl, cnt - 1);
-        cum += __builtin_amdgcn_readlane(incl, kWaveSize - 1);
-        if (cnt < kWaveSize) break;
-    }
-    b_out = found_b;
-    cum_out = found_cum;
-}
-
-// Range boundaries of the flat tile space.  Worker w's share is proportional to 1024 + skew for even w and
-// 1024 - skew for odd w: workgroups go to the eight XCDs round-robin, and under load the odd XCD of every XCD
-// pair delivers 3-4 % less bandwidth than the even one (per-worker exit times, grouped by XCC_ID), so
-// equal shares would leave the even XCDs idle at the end.  The cumulative weight of workers [0, w) is
-// 1024 w + skew (w & 1).  Ranges of fewer than 64 tiles are not skewed.
-__device__ __forceinline__ int effective_skew(int64_t T, int num_workers, int skew) {
-    return T >= 64 * (int64_t)num_workers ? skew : 0;
-}
-__device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_workers, int skew) {
-    const int64_t total = 1024 * (int64_t)num_workers + skew * (num_workers & 1);
-    return T * (1024 * (int64_t)worker + skew * (worker & 1)) / total;
-}
-// Last worker whose range starts at or before flat tile x (0 <= x < T).
-__device__ __forceinline__ int range_owner(int64_t x, int64_t T, int num_workers, int skew) {
-    int w = (int)(x * num_workers / T);
-    while (w > 0 && range_start(w, T, num_workers, skew) > x) --w;
-    while (w + 1 < num_workers && range_start(w + 1, T, num_workers, skew) <= x) ++w;
-    return w;
-}
-// XCC_ID field (bits 3:0) of hardware register 20: the XCD this wave runs on.
-__device__ __forceinline__ int xcc_id() { return (int)__builtin_amdgcn_s_getreg((3 << 11) | 20); }
-
-// KV8: the caches hold FP8 E4M3 codes (one byte per element); q and out are of type E.
-template <Elem E, int D, int BS, int PD, bool KV8>
+template <Elem E, int D, int BS, int PD>
 __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     using G_ = Geo<D>;
     constexpr int NS = PD + 1;                  // LDS stages of the wave
     constexpr int TPB = BS / kTileTokens;       // 16-token tiles per KV block
     constexpr int KJ = G_::kKSteps, CB = G_::kColBlocks;
     constexpr int kRowBytes = G_::kRowBytes, kTileBytes = G_::kTileBytes, kStageBytes = G_::kStageBytes;
-    // what is fetched: the 16-bit tile itself, or the raw 8-bit tile (half the bytes, rows of D bytes)
-    constexpr int kFetchTile = KV8 ? kTileBytes / 2 : kTileBytes;
-    constexpr int kFetchStage = 2 * kFetchTile;
-    constexpr int kElemBytes = KV8 ? 1 : 2;
-    constexpr int LPT = kFetchTile / 1024;      // wave-wide 1 KB fetches per K (or V) tile
+    constexpr int LPT = kTileBytes / 1024;      // wave-wide 1 KB fetches per K (or V) tile
     constexpr int LOADS = 2 * LPT;              // per tile pair
-    constexpr int kImage = NS * kFetchStage;    // KV8: byte offset of the widened V tile behind the ring
-    // KV8, raw K tile: rows of D bytes, RP rows per 256 bytes of LDS, CR 16-byte chunks per row; chunk index XOR
-    // (row / RP) % CR spreads the 8-byte operand reads of 16 rows over all banks
-    constexpr int kRawRP = 256 / D, kRawCR = D / 16;
     constexpr int kPartialStride = G_::kPartialStride;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -340,7 +136,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     const_i32_ptr bt = (const_i32_ptr)p.block_tables;
 
     // ---- this worker's range of the flat tile space
-    const int total = scan_total(cl, p.B, max_len, lane);
+    const int total = scan_total(cl, p.B, max_len, lane, kTileShift);
     const int64_t T = (int64_t)total * Hkv;
     // with fewer tiles than workers only the first T workers get a (one-tile) range, so that every active
     // worker's range is non-empty
@@ -352,10 +148,10 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     Cursor ca;
     {
         int b0, cum0;
-        scan_locate(cl, p.B, max_len, lane, Hkv, r0, b0, cum0);
+        scan_locate(cl, p.B, max_len, lane, kTileShift, Hkv, r0, b0, cum0);
         ca.b = b0;
         ca.n = clamp_len(cl[b0], max_len);
-        ca.ntiles = tiles_of(ca.n);
+        ca.ntiles = tiles_of(ca.n, kTileShift);
         const int rem = (int)(r0 - (int64_t)Hkv * cum0);
         ca.kvh = rem / ca.ntiles;
         ca.j = rem - ca.kvh * ca.ntiles;
@@ -368,7 +164,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         do {
             ++c.b;
             c.n = clamp_len(cl[c.b], max_len);
-            c.ntiles = tiles_of(c.n);
+            c.ntiles = tiles_of(c.n, kTileShift);
         } while (c.ntiles == 0 && c.b + 1 < p.B);
     };
 
@@ -389,38 +185,12 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     // ---- per-lane byte offsets, loop invariant
     // fetch r of a tile lands kRowsPerLoad rows; this lane lands row t = r * kRowsPerLoad + lane / kChunks at
     // stored chunk lane % kChunks, so it fetches chunk (stored ^ swizzle(t)) of row t
-    // (8-bit cache: the raw V tile is copied as it is, fetch r takes bytes 1024 r + 16 lane .. + 16; the raw K
-    // tile is chunk-swizzled for the operand reads)
     uint32_t koff[LPT], voff[LPT];
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
-        if constexpr (KV8) {
-            const int x = lane + 64 * r, t = x / kRawCR, stored = x % kRawCR;
-            koff[r] = t * D + ((stored ^ ((t / kRawRP) % kRawCR)) << 4);
-            voff[r] = r * 1024 + lane * 16;
-        } else {
-            const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
-            koff[r] = t * kRowBytes + ((stored ^ G_::swz_k(t)) << 4);
-            voff[r] = t * kRowBytes + ((stored ^ G_::swz_v(t)) << 4);
-        }
-    }
-    // 8-bit cache, widening of V: this lane takes raw 16-byte chunks lane + 64 r of the V tile; chunk x holds
-    // elements 16 (x % (D/16)) .. + 16 of row x / (D/16), which become the two 16-byte chunks 2 (x % (D/16)) and + 1
-    // of that row of the image, stored at the swizzled positions the transpose reads expect.  (The image keeps
-    // the place of the V tile in a 16-bit stage: its base is kImage - kTileBytes.)
-    uint32_t img_v[LPT][2];
-    // 8-bit cache, K operand of MFMA j straight from the raw tile: row lr, bytes 32 j + 8 lq .. + 8
-    uint32_t kraw[KJ];
-    if constexpr (KV8) {
-#pragma unroll
-        for (int r = 0; r < LPT; ++r) {
-            const int x = lane + 64 * r, t = x / (D / 16), c2 = 2 * (x % (D / 16));
-#pragma unroll
-            for (int h = 0; h < 2; ++h) img_v[r][h] = kImage + t * kRowBytes + (((c2 + h) ^ G_::swz_v(t)) << 4);
-        }
-#pragma unroll
-        for (int j = 0; j < KJ; ++j)
-            kraw[j] = lr * D + (((2 * j + lq / 2) ^ ((lr / kRawRP) % kRawCR)) << 4) + ((lq % 2) << 3);
+        const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
+        koff[r] = t * kRowBytes + ((stored ^ G_::swz_k(t)) << 4);
+        voff[r] = t * kRowBytes + ((stored ^ G_::swz_v(t)) << 4);
     }
     // K read for MFMA j: row lr, logical chunk 4j + lq  ->  stored chunk (4j + lq) ^ swizzle(lr)
     uint32_t kread[KJ];
@@ -441,10 +211,10 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     auto issue = [&](const Cursor& c, int stage) {   // asynchronous fetch of one K tile and one V tile into a stage
         int phys = bt[(int64_t)c.b * p.bt_stride_b + c.j / TPB];   // only entries of tiles inside the range are read
         phys = __builtin_amdgcn_readfirstlane(min(max(phys, 0), p.NBLK - 1));
-        const int sub = (c.j % TPB) * kFetchTile;
-        const unsigned char* kt = kcache + ((int64_t)phys * p.kv_stride_blk + (int64_t)c.kvh * p.kv_stride_h) * kElemBytes + sub;
-        const unsigned char* vt_ = vcache + ((int64_t)phys * p.v_stride_blk + (int64_t)c.kvh * p.v_stride_h) * kElemBytes + sub;
-        unsigned char* dst = smem + stage * kFetchStage;
+        const int sub = (c.j % TPB) * kTileBytes;
+        const unsigned char* kt = kcache + ((int64_t)phys * p.kv_stride_blk + (int64_t)c.kvh * p.kv_stride_h) * 2 + sub;
+        const unsigned char* vt_ = vcache + ((int64_t)phys * p.v_stride_blk + (int64_t)c.kvh * p.v_stride_h) * 2 + sub;
+        unsigned char* dst = smem + stage * kStageBytes;
         // every KV byte is used once: the fetches carry the non-temporal hint so that they do not displace
         // anything in L2 / the memory-side cache (the paper's eviction-priority remark, Section 3.3); measured
         // 184 -> 164 us on the Llama-3-8B-shaped batch
@@ -453,7 +223,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             __builtin_amdgcn_global_load_lds(KVP_GLOBAL(kt + koff[r]), KVP_LDS(dst + r * 1024), 16, 0, kAuxNonTemporal);
 #pragma unroll
         for (int r = 0; r < LPT; ++r)
-            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kFetchTile + r * 1024), 16, 0, kAuxNonTemporal);
+            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kTileBytes + r * 1024), 16, 0, kAuxNonTemporal);
     };
 
     float4v o[CB];
@@ -493,40 +263,10 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             }
         }
         asm volatile("" ::: "memory");
-        uint32_t st = ring_addr + stage * kFetchStage;
+        const uint32_t st = ring_addr + stage * kStageBytes;
         u32x4 ka[KJ];
         u32x2 va[CB];
-        if constexpr (KV8) {
-            // raw K operands (8 codes per lane and MFMA) and the raw V tile, then V widened into the image; LDS
-            // executes a wave's operations in order, so the transpose reads below see it, and the previous tile's
-            // reads are long complete
-            u32x2 kr[KJ];
-            u32x4 raw[LPT];
-#pragma unroll
-            for (int j = 0; j < KJ; ++j) lds_read_raw64(kr[j], st + kraw[j]);
-#pragma unroll
-            for (int r = 0; r < LPT; ++r) lds_read_raw(raw[r], st + kFetchTile + r * 1024 + lane * 16);
-            lds_wait_raw(kr, raw);
-#pragma unroll
-            for (int r = 0; r < LPT; ++r) {
-                const uint32_t w0 = raw[r][0], w1 = raw[r][1], w2 = raw[r][2], w3 = raw[r][3];
-                const u32x2 e0 = widen_fp8x4<E>(w0), e1 = widen_fp8x4<E>(w1), e2 = widen_fp8x4<E>(w2), e3 = widen_fp8x4<E>(w3);
-                const uint32_t a0 = e0[0], a1 = e0[1], a2 = e1[0], a3 = e1[1], b0 = e2[0], b1 = e2[1], b2 = e3[0], b3 = e3[1];
-                lds_write_b128(ring_addr + img_v[r][0], u32x4{a0, a1, a2, a3});
-                lds_write_b128(ring_addr + img_v[r][1], u32x4{b0, b1, b2, b3});
-            }
-            st = ring_addr + kImage - kTileBytes;
-#pragma unroll
-            for (int c4 = 0; c4 < CB; c4 += 4)
-                lds_read_tr16_x4(va[c4], va[c4 + 1], va[c4 + 2], va[c4 + 3], st + vread[c4], st + vread[c4 + 1], st + vread[c4 + 2], st + vread[c4 + 3]);
-#pragma unroll
-            for (int j = 0; j < KJ; ++j) {
-                const uint32_t w0 = kr[j][0], w1 = kr[j][1];
-                const u32x2 e0 = widen_fp8x4<E>(w0), e1 = widen_fp8x4<E>(w1);
-                const uint32_t a0 = e0[0], a1 = e0[1], a2 = e1[0], a3 = e1[1];
-                ka[j] = u32x4{a0, a1, a2, a3};
-            }
-        } else {
+        {
             // ---- issue every LDS read of the tile: the K operands, then the transposed V operands
             if constexpr (KJ == 4) lds_read_b128_x4(ka[0], ka[1], ka[2], ka[3], st + kread[0], st + kread[1], st + kread[2], st + kread[3]);
             else lds_read_b128_x2(ka[0], ka[1], st + kread[0], st + kread[1]);
@@ -651,7 +391,7 @@ __global__ __launch_bounds__(D) void attn_finalize_kernel(AttnParams p, int bs) 
     int total = 0, cum = 0, nt = 0;
     for (int base = 0; base < p.B; base += kWaveSize) {
         const int idx = base + lane;
-        const int t = idx < p.B ? tiles_of(clamp_len(cl[idx], max_len)) : 0;
+        const int t = idx < p.B ? tiles_of(clamp_len(cl[idx], max_len), p.tile_shift) : 0;
         total += wave_sum_i32(t);
         cum += wave_sum_i32(idx < b ? t : 0);
         if (b >= base && b < base + kWaveSize) nt = __builtin_amdgcn_readlane(t, b - base);
@@ -704,37 +444,37 @@ __global__ __launch_bounds__(D) void attn_finalize_kernel(AttnParams p, int bs) 
     orow[c] = pack1<E>(num / den * p.out_scale);
 }
 
-template <Elem E, int D, int BS, int PD, bool KV8>
+template <Elem E, int D, int BS, int PD>
 static int launch_one(const AttnParams& p, hipStream_t stream) {
-    const size_t lds = (size_t)mfma_worker_lds_bytes(PD, D, KV8);
-    auto kern = attn_mfma_kernel<E, D, BS, PD, KV8>;
+    const size_t lds = (size_t)mfma_worker_lds_bytes(PD, D);
+    auto kern = attn_mfma_kernel<E, D, BS, PD>;
     hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), lds, stream, p);
     return 0;
 }
 
-template <Elem E, int D, int BS, bool KV8>
+template <Elem E, int D, int BS>
 static int launch_pd(const AttnParams& p, hipStream_t stream) {
     switch (p.prefetch_distance) {
-        case 0: return launch_one<E, D, BS, 0, KV8>(p, stream);
-        case 1: return launch_one<E, D, BS, 1, KV8>(p, stream);
-        case 2: return launch_one<E, D, BS, 2, KV8>(p, stream);
-        case 3: return launch_one<E, D, BS, 3, KV8>(p, stream);
-        case 4: return launch_one<E, D, BS, 4, KV8>(p, stream);
+        case 0: return launch_one<E, D, BS, 0>(p, stream);
+        case 1: return launch_one<E, D, BS, 1>(p, stream);
+        case 2: return launch_one<E, D, BS, 2>(p, stream);
+        case 3: return launch_one<E, D, BS, 3>(p, stream);
+        case 4: return launch_one<E, D, BS, 4>(p, stream);
         default: return -1;
     }
 }
 
-template <Elem E, bool KV8>
+template <Elem E>
 static int launch_shape(const AttnParams& p, int d, int bs, hipStream_t stream) {
-    if (d == 128) return bs == 16 ? launch_pd<E, 128, 16, KV8>(p, stream) : launch_pd<E, 128, 32, KV8>(p, stream);
-    return bs == 16 ? launch_pd<E, 64, 16, KV8>(p, stream) : launch_pd<E, 64, 32, KV8>(p, stream);
+    if (d == 128) return bs == 16 ? launch_pd<E, 128, 16>(p, stream) : launch_pd<E, 128, 32>(p, stream);
+    return bs == 16 ? launch_pd<E, 64, 16>(p, stream) : launch_pd<E, 64, 32>(p, stream);
 }
 
-// LDS bytes one worker (wave) holds at a prefetch distance: its ring of fetched tile pairs and, for an 8-bit
-// cache (ring stages of half the size), the widened image of the V tile being computed.
-int mfma_worker_lds_bytes(int prefetch_distance, int d, bool kv8) {
+// LDS bytes one worker (wave) holds at a prefetch distance: its ring of fetched tile pairs.  (The same for an
+// 8-bit cache, whose tiles hold twice the tokens in the same bytes.)
+int mfma_worker_lds_bytes(int prefetch_distance, int d) {
     const int stage = d == 128 ? Geo<128>::kStageBytes : Geo<64>::kStageBytes;
-    return kv8 ? (prefetch_distance + 2) * (stage / 2) : (prefetch_distance + 1) * stage;
+    return (prefetch_distance + 1) * stage;
 }
 
 // Bytes of partial storage for a launch with this many workers.
@@ -769,15 +509,15 @@ __global__ __launch_bounds__(kWaveSize) void attn_touch_kernel(AttnParams p, int
     const int max_len = p.MB * BS;
     const_i32_ptr cl = (const_i32_ptr)p.context_lens;
     const_i32_ptr bt = (const_i32_ptr)p.block_tables;
-    const int total = scan_total(cl, p.B, max_len, lane);
+    const int total = scan_total(cl, p.B, max_len, lane, kTileShift);
     const int64_t T = (int64_t)total * Hkv;
     const int nw = T < p.num_workers ? (int)T : p.num_workers;
     if (worker >= nw) return;
     const int skew = effective_skew(T, nw, p.xcd_skew);
     const int64_t r0 = range_start(worker, T, nw, skew), r1 = range_start(worker + 1, T, nw, skew);
     int b0, cum0;
-    scan_locate(cl, p.B, max_len, lane, Hkv, r0, b0, cum0);
-    int b = b0, n = clamp_len(cl[b0], max_len), ntiles = tiles_of(n);
+    scan_locate(cl, p.B, max_len, lane, kTileShift, Hkv, r0, b0, cum0);
+    int b = b0, n = clamp_len(cl[b0], max_len), ntiles = tiles_of(n, kTileShift);
     const int rem = (int)(r0 - (int64_t)Hkv * cum0);
     int kvh = rem / ntiles, j = rem - kvh * ntiles;
     uint32_t acc = 0;
@@ -796,7 +536,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_touch_kernel(AttnParams p, int
                     do {
                         ++b;
                         n = clamp_len(cl[b], max_len);
-                        ntiles = tiles_of(n);
+                        ntiles = tiles_of(n, kTileShift);
                     } while (ntiles == 0 && b + 1 < p.B);
                 }
             }
@@ -819,12 +559,12 @@ int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* s
 }
 
 // Returns 0 or -1 (no such instantiation).
-int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, bool kv8, hipStream_t stream) {
+int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream) {
     if (p.num_workers < 1 || p.num_workers > kMaxMfmaWorkers) return -1;
     if (d != 64 && d != 128) return -1;
     if (bs != 16 && bs != 32) return -1;
-    if (kv8) return elem == (int)Elem::F16 ? launch_shape<Elem::F16, true>(p, d, bs, stream) : launch_shape<Elem::BF16, true>(p, d, bs, stream);
-    return elem == (int)Elem::F16 ? launch_shape<Elem::F16, false>(p, d, bs, stream) : launch_shape<Elem::BF16, false>(p, d, bs, stream);
+    if (p.tile_shift != kTileShift) return -1;
+    return elem == (int)Elem::F16 ? launch_shape<Elem::F16>(p, d, bs, stream) : launch_shape<Elem::BF16>(p, d, bs, stream);
 }
 
 }  // namespace kvp

@@ -53,18 +53,18 @@ int num_cus() {     // of the current device
 // unit at any time; beyond that throughput falls again (measured: 64-96 KB in flight costs 4-8 %).  A wave
 // keeps max(1, distance) tile pairs of 8 KB (head_dim 128) or 4 KB (head_dim 64) in flight, so deep look-ahead
 // wants few waves and no look-ahead wants many; head_dim 64 needs at least four waves to keep up with the
-// arithmetic of its smaller tiles.  An 8-bit cache halves the bytes of a tile and adds the widening to the
-// arithmetic, so it wants more waves for both reasons (measured: 12 waves without look-ahead and 6 with at
-// head_dim 128, 16 and 12 at head_dim 64; 10 or 13 waves, uneven over the four SIMDs, are 25 % slower, so its
-// count is kept even).  Always capped by the LDS the rings need.
+// arithmetic of its smaller tiles.  An 8-bit cache has tile pairs of the same bytes (32 tokens) and twice the
+// arithmetic per byte (the widening included): two waves cannot keep up (measured 120 us against 90 us with six
+// on the Llama-3-8B-shaped batch), so it runs six waves (head_dim 128) or eight to twelve (head_dim 64) at every
+// distance the LDS allows, and four where five would fit (an odd count, uneven over the four SIMDs, is 40 %
+// slower).  Always capped by the LDS the rings need.
 int waves_per_cu(int prefetch_distance, int d, bool kv8) {
-    const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance, d, kv8);
+    const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance, d);
     int w = g_waves_per_cu.load();
     if (w <= 0) {
-        if (kv8) w = d == 128 ? (prefetch_distance == 0 ? 12 : 6) : (prefetch_distance == 0 ? 16 : 12);
+        if (kv8) w = d == 128 ? (prefetch_distance <= 2 ? 6 : 4) : (prefetch_distance == 0 ? 12 : 8);
         else if (d == 128) w = prefetch_distance <= 1 ? 6 : 2;
         else w = prefetch_distance <= 1 ? 8 : 4;
-        if (kv8 && w > lds_limit) w = lds_limit > 8 ? (lds_limit & ~3) : (lds_limit & ~1);   // even over the four SIMDs
     }
     w = w < lds_limit ? w : lds_limit;
     w = w < kMaxWavesPerCU ? w : kMaxWavesPerCU;
@@ -169,6 +169,7 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.B = (int)B; p.Hq = (int)Hq; p.Hkv = num_kv_heads; p.G = G;
     p.MB = (int)MB; p.NBLK = (int)k_cache->shape[0];
     p.prefetch_distance = prefetch_distance;
+    p.tile_shift = kv8 ? 5 : 4;
     p.scale_log2e = scale * kvp::kLog2e * (kv8 ? k_scale : 1.0f);
     p.out_scale = kv8 ? v_scale : 1.0f;
     r->elem = q->dtype; r->d = (int)d; r->bs = block_size; r->kv8 = kv8;
@@ -213,7 +214,7 @@ int run_attn(const Resolved& r, hipStream_t stream) {
     if (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity && (g_prof_seen++ % g_prof_every) == 0) slot = g_prof_calls++;
     prof_lock.unlock();
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), stream);
-    if (kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, r.kv8, stream) != 0)
+    if ((r.kv8 ? kvp::launch_attn_kv8(r.p, r.elem, r.d, r.bs, stream) : kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, stream)) != 0)
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);

@@ -30,6 +30,7 @@ struct AttnParams {
     int32_t NBLK;             // physical blocks in the cache
     int32_t prefetch_distance;
     int32_t num_workers;      // persistent waves (workers) of the launch
+    int32_t tile_shift;       // log2 of the tokens per tile of the flat tile space: 4 (16-bit caches) or 5 (8-bit)
     int32_t xcd_skew;         // per-1024 skew of the range sizes between even and odd workers (XCDs)
     float scale_log2e;        // scale * log2(e) (* k_scale for an 8-bit cache): logits live in the base-2 domain
     float out_scale;          // multiplies every output row: 1, or v_scale for an 8-bit cache
@@ -49,7 +50,8 @@ __device__ __forceinline__ uint16_t pack1(float f) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, bool kv8, hipStream_t stream);
+int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
+int launch_attn_kv8(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_finalize_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* sink, hipStream_t stream);
 int launch_layer_gemm(const void* x, const void* w, void* y, int M, int K, int N, int64_t ldx, int64_t ldw,
@@ -59,7 +61,7 @@ int launch_layer_gemm_packed(const void* x, const void* wp, void* y, int M, int 
 size_t layer_gemm_packed_partial_bytes(int N);
 void launch_zero_words(int* p, int n, hipStream_t stream);
 constexpr size_t kGemmTicketBytes = 4096;      // head of the workspace: one ticket word per 128-column tile of the dense layer
-int mfma_worker_lds_bytes(int prefetch_distance, int d, bool kv8);
+int mfma_worker_lds_bytes(int prefetch_distance, int d);
 size_t mfma_partial_bytes(int num_workers, int G, int d);
 constexpr int kMaxMfmaWorkers = 4096;
 

@@ -61,12 +61,12 @@ def test_waves_per_cu_follow_the_lds_budget():
     assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [8, 8, 4, 4, 4]
     # an explicit request is capped by LDS: a worker's ring is (distance + 1) x 8 KB at head_dim 128 (4 KB at
     # 64), a compute unit has 160 KB
-    # 8-bit cache: ring stages of half the size plus one widened V tile; more waves, kept even over the SIMDs
-    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [12, 6, 6, 6, 6]
-    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 64) for d in range(5)] == [16, 12, 12, 12, 12]
+    # 8-bit cache: tile pairs of the same bytes (32 tokens), twice the arithmetic per byte: more waves
+    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [6, 6, 6, 4, 4]
+    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 64) for d in range(5)] == [12, 8, 8, 8, 8]
     kv.kv_decode_set_waves_per_cu(16)
     try:
-        assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [16, 13, 10, 8, 6]
+        assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [16, 10, 6, 5, 4]
         assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [16, 10, 6, 5, 4]
         assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [16, 16, 13, 10, 8]
         with pytest.raises(kv.KVError):

@@ -56,6 +56,19 @@ def test_shapes_groups_and_query_types(dtype, d, bs, G):
     compare(run_hip(c), run_oracle(c), f"{dtype} d{d} bs{bs} G{G}")
 
 
+@pytest.mark.parametrize("d,bs", [(128, 16), (128, 32), (64, 16), (64, 32)])
+def test_lengths_around_the_32_token_tiles(d, bs):
+    """The 8-bit kernel walks 32-token tiles, which span two 16-token KV blocks: contexts that end in the first or
+    the second block of their last tile, on and next to every boundary, with poisoned slack and table entries."""
+    cfg = dict(Hq=8, Hkv=2, d=d, bs=bs, dtype="bf16")
+    lens = [16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 2, 0, 95, 96, 97, 1023, 1040]
+    c = synth.make_case_kv8(cfg, 77 + d + bs, DEV, poison=True, lens=lens, k_scale=0.75, v_scale=1.25)
+    for pd in (0, 2):
+        got = run_hip(c, pd)
+        compare(got, run_oracle(c), f"d{d} bs{bs} distance {pd}")
+        assert not got[12].any()
+
+
 @pytest.mark.parametrize("pd", list(range(0, kv.KV_MAX_PREFETCH_DISTANCE + 1)))
 def test_every_prefetch_distance_gives_the_same_bits(pd):
     cfg = dict(Hq=8, Hkv=2, d=128, bs=16, dtype="bf16")
