@@ -408,7 +408,7 @@ __global__ __launch_bounds__(D) void attn_finalize_kernel(AttnParams p, int bs) 
     const int w1 = range_owner(end - 1, T, nw, skew);   // last worker whose range starts before end
     if (w0 == w1) return;                           // one worker covered the unit and wrote the rows itself
     const int np = w1 - w0 + 1;
-    const int slot_first = range_start(w0, T, nw, skew) < a ? 1 : 0;
+    const int slot_first = range_starts_before(w0, a, T, nw, skew) ? 1 : 0;
     const float* first_row = p.partials + ((int64_t)(w0 * 2 + slot_first) * G + g) * PS;
     const float* later_rows = p.partials + ((int64_t)(w0 * 2) * G + g) * PS;     // + i * 2 * G * PS for piece i >= 1
 
