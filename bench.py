@@ -303,7 +303,7 @@ def main():
 
     if args.kv8:
         result["config"]["waves_per_cu"] = kv.kv_decode_get_waves_per_cu_kv8(pd_on, cfg["d"])
-        result["roofline"]["kernel"] = "attn_mfma_kernel, 8-bit cache variant"
+        result["roofline"]["kernel"] = "attn_kv8_kernel (main attention kernel, 8-bit cache)"
         print(json.dumps(result), flush=True)
         return
     if not args.no_extra:

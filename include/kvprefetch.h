@@ -152,8 +152,9 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
  */
 int kv_decode_set_waves_per_cu(int waves);
 int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
-/* The same for kv_decode_attn_kv8 (ring stages of half the size plus one widened V tile per worker;
- * automatic choice at head_dim 128: 12 waves at distance 0, 6 beyond; at head_dim 64: 16 and 12). */
+/* The same for kv_decode_attn_kv8 (stages of the same bytes, holding 32 tokens; twice the arithmetic
+ * per byte, so more waves: at head_dim 128 6 waves up to distance 2 and 4 beyond, at head_dim 64 12
+ * waves at distance 0 and 8 beyond). */
 int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
 
 /*
