@@ -204,6 +204,17 @@ size_t kv_block_bytes(int elem_bytes, int head_dim, int block_size);
  * units_per_wg is the number of waves of a workgroup (N_thread / 32 in the paper). */
 size_t kv_iter_working_set_bytes(size_t block_bytes, int units_per_wg, int H, int B);
 
+/*
+ * The attention kernels' partition of the flat tile space (all tiles of all (sequence, kv head)
+ * units in order; Algorithm 1's block range [s, e) of a warp becomes one contiguous range per
+ * persistent wave), computed on the host by the code the kernels run.  `tiles` >= 1 tiles are cut
+ * among min(workers, tiles) workers; xcd_skew as in kv_decode_set_xcd_skew.
+ * kv_worker_range: first tile and end (one past the last) of worker's range; status.
+ * kv_worker_of_tile: the worker whose range holds `tile`, or -1 for invalid arguments.
+ */
+int kv_worker_range(int64_t tiles, int workers, int xcd_skew, int worker, int64_t* first, int64_t* end);
+int kv_worker_of_tile(int64_t tiles, int workers, int xcd_skew, int64_t tile);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     kv_decode_set_waves_per_cu,
     kv_decode_get_waves_per_cu,
     kv_block_bytes,
+    kv_worker_range,
+    kv_worker_of_tile,
     kv_profile_enable,
     kv_profile_read,
     kv_iter_working_set_bytes,

@@ -43,7 +43,7 @@ EXPORTS = [
     "kv_decode_attn", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
     "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
-    "kv_block_bytes", "kv_iter_working_set_bytes", "kv_profile_enable", "kv_profile_read",
+    "kv_block_bytes", "kv_iter_working_set_bytes", "kv_worker_range", "kv_worker_of_tile", "kv_profile_enable", "kv_profile_read",
 ]
 
 
@@ -90,6 +90,11 @@ def load_library():
             lib.kv_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
             lib.kv_last_error.restype = ctypes.c_char_p
             lib.kv_version.restype = ctypes.c_int
+            lib.kv_worker_range.restype = ctypes.c_int
+            lib.kv_worker_range.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+            lib.kv_worker_of_tile.restype = ctypes.c_int
+            lib.kv_worker_of_tile.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int64]
             lib.kv_block_bytes.restype = ctypes.c_size_t
             lib.kv_block_bytes.argtypes = [ctypes.c_int] * 3
             lib.kv_iter_working_set_bytes.restype = ctypes.c_size_t
@@ -280,6 +285,16 @@ def pack_weights(w: torch.Tensor, layout: str = "operand") -> torch.Tensor:
     # W[ks, lq, j, t, nb, lr] -> Wp[t, ks, nb, (lq, lr), j]
     return (w.reshape(K // 32, 4, 8, N // 64, 4, 16).permute(3, 0, 4, 1, 5, 2).contiguous()
             .reshape(N // 64, K // 32, 4, 64, 8))
+
+
+def kv_worker_range(tiles: int, workers: int, xcd_skew: int, worker: int):
+    first, end = ctypes.c_int64(), ctypes.c_int64()
+    _check(load_library().kv_worker_range(tiles, workers, xcd_skew, worker, ctypes.byref(first), ctypes.byref(end)))
+    return first.value, end.value
+
+
+def kv_worker_of_tile(tiles: int, workers: int, xcd_skew: int, tile: int) -> int:
+    return int(load_library().kv_worker_of_tile(tiles, workers, xcd_skew, tile))
 
 
 def kv_block_bytes(elem_bytes: int, head_dim: int, block_size: int) -> int:

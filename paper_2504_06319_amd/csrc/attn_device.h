@@ -161,32 +161,32 @@ __device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len
 // pair delivers 3-4 % less bandwidth than the even one (per-worker exit times, grouped by XCC_ID), so
 // equal shares would leave the even XCDs idle at the end.  The cumulative weight of workers [0, w) is
 // 1024 w + skew (w & 1).  Ranges of fewer than 64 tiles are not skewed.
-__device__ __forceinline__ int effective_skew(int64_t T, int num_workers, int skew) {
+__host__ __device__ __forceinline__ int effective_skew(int64_t T, int num_workers, int skew) {
     return T >= 64 * (int64_t)num_workers ? skew : 0;
 }
 // floor(num / den) for 0 <= num < 2^62, 0 < den, quotient below 2^31: a double-precision estimate (error below one)
 // and one exact correction step; an emulated 64-bit integer division costs several times as much.
-__device__ __forceinline__ int64_t floor_div(int64_t num, int64_t den) {
+__host__ __device__ __forceinline__ int64_t floor_div(int64_t num, int64_t den) {
     int64_t q = (int64_t)((double)num / (double)den);
     const int64_t r = num - q * den;
     if (r < 0) --q;
     else if (r >= den) ++q;
     return q;
 }
-__device__ __forceinline__ int64_t range_weight(int worker, int skew) { return 1024 * (int64_t)worker + skew * (worker & 1); }
-__device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_workers, int skew) {
+__host__ __device__ __forceinline__ int64_t range_weight(int worker, int skew) { return 1024 * (int64_t)worker + skew * (worker & 1); }
+__host__ __device__ __forceinline__ int64_t range_start(int worker, int64_t T, int num_workers, int skew) {
     return floor_div(T * range_weight(worker, skew), range_weight(num_workers, skew));
 }
 // Last worker whose range starts at or before flat tile x (0 <= x < T): range_start(w) <= x exactly when
 // T weight(w) < (x + 1) total, i.e. weight(w) <= floor(((x + 1) total - 1) / T).
-__device__ __forceinline__ int range_owner(int64_t x, int64_t T, int num_workers, int skew) {
+__host__ __device__ __forceinline__ int range_owner(int64_t x, int64_t T, int num_workers, int skew) {
     const int64_t limit = floor_div((x + 1) * range_weight(num_workers, skew) - 1, T);
     int w = (int)(limit >> 10);
     if (range_weight(w, skew) > limit) --w;
     return w < num_workers - 1 ? w : num_workers - 1;
 }
 // Whether range_start(worker) < x, without a division.
-__device__ __forceinline__ bool range_starts_before(int worker, int64_t x, int64_t T, int num_workers, int skew) {
+__host__ __device__ __forceinline__ bool range_starts_before(int worker, int64_t x, int64_t T, int num_workers, int skew) {
     return T * range_weight(worker, skew) < x * range_weight(num_workers, skew);
 }
 // XCC_ID field (bits 3:0) of hardware register 20: the XCD this wave runs on.

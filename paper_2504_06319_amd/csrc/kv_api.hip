@@ -1,7 +1,7 @@
 // C ABI of kvprefetch: argument validation, error reporting, partition planning and
 // kernel dispatch.  Host code only; the kernels live in the other sources.
 #include "../../include/kvprefetch.h"
-#include "kv_common.h"
+#include "attn_device.h"
 
 #include <cmath>
 
@@ -459,6 +459,26 @@ int kv_profile_read(double* main_ms_sum, int* calls) {
 const char* kv_last_error(void) { return g_err; }
 
 int kv_version(void) { return 100; }
+
+int kv_worker_range(int64_t tiles, int workers, int xcd_skew, int worker, int64_t* first, int64_t* end) {
+    if (tiles < 1 || tiles > ((int64_t)1 << 40) || workers < 1 || workers > kvp::kMaxMfmaWorkers || xcd_skew < 0 ||
+        xcd_skew > 256 || !first || !end)
+        return fail(KV_ERR_INVALID, "kv_worker_range: invalid argument");
+    const int nw = tiles < workers ? (int)tiles : workers;
+    if (worker < 0 || worker >= nw) return fail(KV_ERR_INVALID, "kv_worker_range: worker %d of %d", worker, nw);
+    const int skew = kvp::effective_skew(tiles, nw, xcd_skew);
+    *first = kvp::range_start(worker, tiles, nw, skew);
+    *end = kvp::range_start(worker + 1, tiles, nw, skew);
+    return KV_OK;
+}
+
+int kv_worker_of_tile(int64_t tiles, int workers, int xcd_skew, int64_t tile) {
+    if (tiles < 1 || tiles > ((int64_t)1 << 40) || workers < 1 || workers > kvp::kMaxMfmaWorkers || xcd_skew < 0 ||
+        xcd_skew > 256 || tile < 0 || tile >= tiles)
+        return -1;
+    const int nw = tiles < workers ? (int)tiles : workers;
+    return kvp::range_owner(tile, tiles, nw, kvp::effective_skew(tiles, nw, xcd_skew));
+}
 
 size_t kv_block_bytes(int elem_bytes, int head_dim, int block_size) {
     if (elem_bytes <= 0 || head_dim <= 0 || block_size <= 0) return 0;
