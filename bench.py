@@ -82,6 +82,40 @@ def layer_stack(kv, torch, synth, dev, steps, warmup, pd, cross, layers=None):
     return ms, kvb, wb, cfg, L
 
 
+def fetch_ceiling(kv, torch, cases, kvb, steps=40, warmup=8):
+    """The memory system's rate for the kernel's own access pattern: the fetch stream of the attention kernel
+    with its arithmetic left out (kv_decode_fetch_probe), beside the attention kernel itself, for a grid of
+    (waves per compute unit, prefetch distance); main-kernel microseconds from the library's HIP events."""
+    def timed(fn, pd):
+        def step(i):
+            c = cases[i % len(cases)]
+            fn(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], c["out"], c["scale"],
+               c["num_kv_heads"], c["block_size"], pd)
+        for i in range(warmup):
+            step(i)
+        kv.kv_profile_enable(steps, 1)
+        torch.cuda.synchronize()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        ms, n = kv.kv_profile_read()
+        kv.kv_profile_enable(0, 1)
+        return ms / n * 1e3
+    rows = []
+    d = cases[0]["q"].shape[2]
+    try:
+        for waves, pd in ((2, 2), (2, 4), (4, 1), (4, 2), (6, 0), (6, 1), (6, 2), (8, 1), (12, 0), (16, 0)):
+            kv.kv_decode_set_waves_per_cu(waves)
+            probe_us, attn_us = timed(kv.kv_decode_fetch_probe, pd), timed(kv.kv_decode_attn, pd)
+            rows.append({"waves_per_cu": kv.kv_decode_get_waves_per_cu(pd, d), "prefetch_distance": pd,
+                         "fetch_only_us": round(probe_us, 1), "fetch_only_GBps": round(kvb / probe_us / 1e3, 0),
+                         "attention_us": round(attn_us, 1), "attention_GBps": round(kvb / attn_us / 1e3, 0)})
+            log(f"[bench] {rows[-1]}")
+    finally:
+        kv.kv_decode_set_waves_per_cu(0)
+    return rows
+
+
 HEATMAP_MODELS = {               # attention shapes of the paper's four models (Section 4.1), head_dim 128, 16-token blocks
     "mha_32q_32kv": (32, 32), "gqa_32q_8kv": (32, 8), "gqa_28q_4kv": (28, 4), "gqa_40q_8kv": (40, 8),
 }
@@ -209,6 +243,9 @@ def main():
                          "profiler runs of that kernel); GB/s then counts the 8-bit bytes")
     ap.add_argument("--worker-timeline", action="store_true",
                     help="print the per-worker entry / exit times of one launch of the main kernel and exit")
+    ap.add_argument("--fetch-ceiling", action="store_true",
+                    help="time the attention kernel's fetch stream without its arithmetic beside the kernel itself "
+                         "over a grid of occupancies and prefetch distances, print the table and exit")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run plain 1 GiB device copies, so a counter run sees a copy kernel of known traffic")
     args = ap.parse_args()
@@ -265,6 +302,12 @@ def main():
         cfg, cases = make_cases(args.workload)
         print(json.dumps({"workload": cfg["name"], "prefetch_distance": pd_on,
                           "worker_timeline": worker_timeline(kv, torch, cases, pd_on)}), flush=True)
+        return
+    if args.fetch_ceiling:
+        cfg, cases = make_cases(args.workload)
+        kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"])
+        print(json.dumps({"workload": cfg["name"], "kv_bytes_per_launch": kvb,
+                          "fetch_ceiling": fetch_ceiling(kv, torch, cases, kvb)}), flush=True)
         return
     if args.layer_stack_only:
         lms, lkvb, lwb, lcfg, L = layer_stack(kv, torch, synth, dev, args.steps, args.warmup, pd_on, args.cross_layer_touch,

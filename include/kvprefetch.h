@@ -75,6 +75,18 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
                    void* stream);
 
 /*
+ * Measurement aid: the fetch stream of kv_decode_attn with the arithmetic left out.  Same
+ * arguments and checks, same worker ranges, block-table lookups and asynchronous tile fetches at
+ * the same prefetch_distance and occupancy; nothing is read back from LDS and nothing is written
+ * (out is untouched, no merge kernel runs).  Its duration is what the memory system takes for
+ * exactly this access pattern: the ceiling the attention kernel's roofline fraction is read
+ * against.  Timed by kv_profile_enable like the main kernel.  16-bit caches only.
+ */
+int kv_decode_fetch_probe(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+                          const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+                          float scale, int num_kv_heads, int block_size, int prefetch_distance, void* stream);
+
+/*
  * The same operation on an 8-bit KV cache (not in the paper: its Eq. 1 has the element size b as
  * a parameter, and halving b halves the bytes the kernel is bound by).  k_cache and v_cache hold
  * OCP FP8 E4M3 codes (dtype KV_FP8_E4M3, one byte per element, same [NBLK, Hkv, bs, d] layout

@@ -41,7 +41,7 @@ class KVTensor(ctypes.Structure):
 
 EXPORTS = [
     "kv_decode_attn", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
-    "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew",
+    "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew", "kv_decode_fetch_probe",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_worker_range", "kv_worker_of_tile", "kv_profile_enable", "kv_profile_read",
 ]
@@ -65,6 +65,8 @@ def load_library():
             lib.kv_decode_attn.restype = ctypes.c_int
             lib.kv_decode_attn.argtypes = [T, T, T, T, T, T, ctypes.c_float, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int, ctypes.c_void_p]
+            lib.kv_decode_fetch_probe.restype = ctypes.c_int
+            lib.kv_decode_fetch_probe.argtypes = lib.kv_decode_attn.argtypes
             lib.kv_decode_attn_kv8.restype = ctypes.c_int
             lib.kv_decode_attn_kv8.argtypes = [T, T, T, T, T, T, ctypes.c_float, ctypes.c_float, ctypes.c_float,
                                                ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
@@ -195,6 +197,18 @@ def kv_decode_attn(q, k_cache, v_cache, block_tables, context_lens, out, scale, 
     _check(lib.kv_decode_attn(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
                               int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))))
     return out
+
+
+def kv_decode_fetch_probe(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
+                          block_size, prefetch_distance=1, stream=None):
+    """The fetch stream of kv_decode_attn without its arithmetic (a measurement aid); writes nothing."""
+    lib = load_library()
+    need = kv_decode_workspace_bytes(q.shape[0], q.shape[1], q.shape[2],
+                                     block_tables.shape[1] * block_size, block_size)
+    _ensure_workspace(q.device, need)
+    descs = [describe(t) for t in (q, k_cache, v_cache, block_tables, context_lens, out)]
+    _check(lib.kv_decode_fetch_probe(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
+                                     int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))))
 
 
 def kv_decode_attn_kv8(q, k_cache, v_cache, block_tables, context_lens, out, scale, k_scale, v_scale,

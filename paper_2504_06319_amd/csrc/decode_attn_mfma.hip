@@ -113,7 +113,10 @@ struct Geo {
 };
 
 
-template <Elem E, int D, int BS, int PD>
+// FETCH_ONLY: the same ranges, cursor and fetch stream with the arithmetic left out (nothing is read from LDS,
+// nothing is written): the memory system's rate for exactly this access pattern, the ceiling the kernel is
+// measured against.
+template <Elem E, int D, int BS, int PD, bool FETCH_ONLY = false>
 __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     using G_ = Geo<D>;
     constexpr int NS = PD + 1;                  // LDS stages of the wave
@@ -263,6 +266,10 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
             }
         }
         asm volatile("" ::: "memory");
+        if constexpr (FETCH_ONLY) {
+            if constexpr (PD > 0) { stage = stage + 1 == NS ? 0 : stage + 1; }
+            continue;
+        }
         const uint32_t st = ring_addr + stage * kStageBytes;
         u32x4 ka[KJ];
         u32x2 va[CB];
@@ -468,6 +475,30 @@ template <Elem E>
 static int launch_shape(const AttnParams& p, int d, int bs, hipStream_t stream) {
     if (d == 128) return bs == 16 ? launch_pd<E, 128, 16>(p, stream) : launch_pd<E, 128, 32>(p, stream);
     return bs == 16 ? launch_pd<E, 64, 16>(p, stream) : launch_pd<E, 64, 32>(p, stream);
+}
+
+template <int D, int BS>
+static int launch_fetch_pd(const AttnParams& p, hipStream_t stream) {
+    auto go = [&](auto kern, int pd) {
+        hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), (size_t)mfma_worker_lds_bytes(pd, D), stream, p);
+        return 0;
+    };
+    switch (p.prefetch_distance) {
+        case 0: return go(attn_mfma_kernel<Elem::BF16, D, BS, 0, true>, 0);
+        case 1: return go(attn_mfma_kernel<Elem::BF16, D, BS, 1, true>, 1);
+        case 2: return go(attn_mfma_kernel<Elem::BF16, D, BS, 2, true>, 2);
+        case 3: return go(attn_mfma_kernel<Elem::BF16, D, BS, 3, true>, 3);
+        case 4: return go(attn_mfma_kernel<Elem::BF16, D, BS, 4, true>, 4);
+        default: return -1;
+    }
+}
+
+// The fetch stream of launch_attn_mfma without its arithmetic; writes nothing.  Returns 0 or -1.
+int launch_fetch_probe(const AttnParams& p, int d, int bs, hipStream_t stream) {
+    if (p.num_workers < 1 || p.num_workers > kMaxMfmaWorkers || p.tile_shift != kTileShift) return -1;
+    if (d == 128) return bs == 16 ? launch_fetch_pd<128, 16>(p, stream) : bs == 32 ? launch_fetch_pd<128, 32>(p, stream) : -1;
+    if (d == 64) return bs == 16 ? launch_fetch_pd<64, 16>(p, stream) : bs == 32 ? launch_fetch_pd<64, 32>(p, stream) : -1;
+    return -1;
 }
 
 // LDS bytes one worker (wave) holds at a prefetch distance: its ring of fetched tile pairs.  (The same for an

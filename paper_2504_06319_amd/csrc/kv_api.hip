@@ -237,6 +237,26 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
     return run_attn(r, (hipStream_t)stream);
 }
 
+int kv_decode_fetch_probe(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+                          const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+                          float scale, int num_kv_heads, int block_size, int prefetch_distance, void* stream) {
+    Resolved r;
+    if (int rc = resolve(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
+                         block_size, prefetch_distance, &r))
+        return rc;
+    std::unique_lock<std::mutex> prof_lock(g_prof_mutex);
+    int slot = -1;
+    if (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity && (g_prof_seen++ % g_prof_every) == 0) slot = g_prof_calls++;
+    prof_lock.unlock();
+    r.p.worker_trace = nullptr;
+    if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), (hipStream_t)stream);
+    if (kvp::launch_fetch_probe(r.p, r.d, r.bs, (hipStream_t)stream) != 0)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_fetch_probe: no kernel for head_dim %d, block_size %d", r.d, r.bs);
+    if (int rc = check_launch("kv_decode_fetch_probe")) return rc;
+    if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), (hipStream_t)stream);
+    return KV_OK;
+}
+
 int kv_decode_attn_kv8(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
                        const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
                        float scale, float k_scale, float v_scale, int num_kv_heads, int block_size,

@@ -51,6 +51,7 @@ __device__ __forceinline__ uint16_t pack1(float f) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
+int launch_fetch_probe(const AttnParams& p, int d, int bs, hipStream_t stream);
 int launch_attn_kv8(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_finalize_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* sink, hipStream_t stream);

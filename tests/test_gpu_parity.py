@@ -280,6 +280,19 @@ def test_full_size_configuration_on_sampled_rows(index):
     assert torch.isfinite(got1.float()).all()
 
 
+@pytest.mark.parametrize("d,bs", [(128, 16), (128, 32), (64, 16), (64, 32)])
+def test_fetch_probe_runs_the_fetch_stream_and_writes_nothing(d, bs):
+    lens = [700, 0, 33, 1500, 16, 4000, 257, 1]
+    c = synth.make_case(_cfg(8, 2, d, bs, "bf16"), 71, DEV, poison=True, lens=lens)
+    out = torch.full_like(c["q"], 7.0)
+    for pd in range(0, kv.KV_MAX_PREFETCH_DISTANCE + 1):
+        kv.kv_decode_fetch_probe(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], out,
+                                 c["scale"], c["num_kv_heads"], c["block_size"], pd)
+    torch.cuda.synchronize()
+    assert (out == 7.0).all()
+    check_case(c, 2, "attention after the probe")
+
+
 def test_worker_timeline_accounts_for_every_tile():
     """Every worker reports its entry / range-located / exit clock readings and its tile count: the counts add
     up to the tiles of the batch (per kv head), the readings are ordered, and the result is unchanged."""
