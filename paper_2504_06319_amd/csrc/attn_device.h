@@ -160,9 +160,9 @@ __device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len
 // 1024 - skew for odd w: workgroups go to the eight XCDs round-robin, and under load the odd XCD of every XCD
 // pair delivers 3-4 % less bandwidth than the even one (per-worker exit times, grouped by XCC_ID), so
 // equal shares would leave the even XCDs idle at the end.  The cumulative weight of workers [0, w) is
-// 1024 w + skew (w & 1).  Ranges of fewer than 64 tiles are not skewed.
+// 1024 w + skew (w & 1).  Ranges of fewer than 16 tiles are not skewed.
 __host__ __device__ __forceinline__ int effective_skew(int64_t T, int num_workers, int skew) {
-    return T >= 64 * (int64_t)num_workers ? skew : 0;
+    return T >= 16 * (int64_t)num_workers ? skew : 0;
 }
 // floor(num / den) for 0 <= num < 2^62, 0 < den, quotient below 2^31: a double-precision estimate (error below one)
 // and one exact correction step; an emulated 64-bit integer division costs several times as much.

@@ -18,7 +18,7 @@ def exact_start(w, tiles, nw, skew):
 
 def cases():
     rng = random.Random(20250408)
-    out = [(1, 1, 0), (1, 512, 20), (511, 512, 20), (512, 512, 20), (64 * 512 - 1, 512, 20), (64 * 512, 512, 20),
+    out = [(1, 1, 0), (1, 512, 20), (511, 512, 20), (512, 512, 20), (16 * 512 - 1, 512, 20), (16 * 512, 512, 20), (64 * 512, 512, 20),
            (126416, 512, 20), (126416, 1536, 20), (63344, 1536, 20), (2**31 - 1, 4096, 256), (2**40, 4095, 255),
            (2**40, 4096, 0), (2**36 + 12345, 1, 20), (100003, 7, 256)]
     for _ in range(300):
@@ -31,7 +31,7 @@ def cases():
 @pytest.mark.parametrize("tiles,workers,skew", cases())
 def test_ranges_partition_the_tile_space_exactly(tiles, workers, skew):
     nw = min(tiles, workers)
-    eff = skew if tiles >= 64 * nw else 0          # short ranges are not skewed
+    eff = skew if tiles >= 16 * nw else 0          # short ranges are not skewed
     rng = random.Random(tiles ^ workers)
     sample = sorted({0, 1, nw // 2, nw - 2, nw - 1} | {rng.randrange(nw) for _ in range(40)})
     prev_end = None
