@@ -109,16 +109,22 @@ def test_empty_batch_rows_single_tokens_and_one_long_sequence():
     compare(run_hip(c), run_oracle(c), "one long sequence")
 
 
-def test_llama3_8b_shape_sampled():
-    """Benchmark configuration 1 with an 8-bit cache at full size; sampled (sequence, head) rows on the oracle."""
-    cfg = synth.CONFIGS[1]
-    c = synth.make_case_kv8(cfg, synth.config_seed(1), DEV)
-    got = run_hip(c, 2)
-    rng = np.random.default_rng(1)
-    pairs = [(int(b), int(h)) for b in rng.choice(cfg["B"], 6, replace=False) for h in rng.choice(cfg["Hq"], 3, replace=False)]
+@pytest.mark.parametrize("index", [1, 2, 3])
+def test_benchmark_configurations_at_full_size_sampled(index):
+    """The benchmark configurations with an 8-bit cache at full size, at the distance bench.py times (1) and
+    without look-ahead; sampled (sequence, head) rows on the oracle, the shortest and the longest sequence included."""
+    cfg = synth.CONFIGS[index]
+    c = synth.make_case_kv8(cfg, synth.config_seed(index), DEV)
+    rng = np.random.default_rng(index)
+    lens = c["lens"]
+    seqs = sorted({int(np.argmin(lens)), int(np.argmax(lens))} | set(rng.integers(0, cfg["B"], 4).tolist()))
+    pairs = [(b, int(h)) for b in seqs for h in rng.choice(cfg["Hq"], 3, replace=False)]
     want = run_oracle(c, pairs)
-    g = got.to(torch.float64).cpu().numpy()
-    compare(np.stack([g[b, h] for b, h in pairs]), want, "configuration 1, 8-bit cache")
+    for pd in (1, 0):
+        got = run_hip(c, pd)
+        assert torch.isfinite(got.float()).all()
+        g = got.to(torch.float64).cpu().numpy()
+        compare(np.stack([g[b, h] for b, h in pairs]), want, f"{cfg['name']}, 8-bit cache, distance {pd}")
 
 
 def test_wrong_cache_type_and_scales_are_rejected():
