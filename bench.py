@@ -243,6 +243,9 @@ def main():
                          "profiler runs of that kernel); GB/s then counts the 8-bit bytes")
     ap.add_argument("--worker-timeline", action="store_true",
                     help="print the per-worker entry / exit times of one launch of the main kernel and exit")
+    ap.add_argument("--l2-touch", type=int, default=0, metavar="TILES",
+                    help="comparison mode: with --prefetch-distance 0, a second wave per worker touches this many tiles "
+                         "per group into L2 ahead of it (the paper's mechanism in place of the LDS ring)")
     ap.add_argument("--fetch-ceiling", action="store_true",
                     help="time the attention kernel's fetch stream without its arithmetic beside the kernel itself "
                          "over a grid of occupancies and prefetch distances, print the table and exit")
@@ -267,6 +270,8 @@ def main():
     torch.cuda.set_device(0)
     if args.waves_per_cu:
         kv.kv_decode_set_waves_per_cu(args.waves_per_cu)
+    if args.l2_touch:
+        kv.kv_decode_set_l2_touch(args.l2_touch)
 
     def make_cases(index, copies=2, kv8=False):
         cfg = synth.CONFIGS[index]
@@ -334,7 +339,8 @@ def main():
                    "head_dim": cfg["d"], "block_size": cfg["bs"],
                    "context_lens": "fixed" if "lens" in cfg else f"uniform{list(cfg['len_range'])}",
                    "kv_bytes_per_step": kvb, "prefetch_distance": pd_on,
-                   "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, cfg["d"])},
+                   "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, cfg["d"]),
+                   **({"l2_touch_tiles": args.l2_touch} if args.l2_touch and pd_on == 0 and not args.kv8 else {})},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "tokens_per_s": cfg["B"] / (ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -170,6 +170,17 @@ int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
 int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
 
 /*
+ * Comparison mode: the paper's own mechanism, prefetch into L2 (its Section 3.2), in place of the
+ * LDS ring.  With tiles > 0, calls of kv_decode_attn (and the layer stack) with prefetch_distance 0
+ * launch every worker with a second wave that walks the same range and touches the K and V tiles
+ * ahead of it into L2 (one dword per 128-byte line), in groups of `tiles` tiles and at most two
+ * groups ahead of the worker; the worker itself fetches, waits and computes as at distance 0 and
+ * finds its lines in L2.  Results are those of distance 0.  0 (the default) switches it off;
+ * 0 .. 8.  Calls with another prefetch_distance and kv_decode_attn_kv8 ignore it.
+ */
+int kv_decode_set_l2_touch(int tiles);
+
+/*
  * Skew of the workers' shares of the tile space between the even and the odd XCD of every XCD
  * pair, in 1/1024: worker w gets 1024 + skew parts when w is even and 1024 - skew when it is odd
  * (workgroups go to the XCDs round-robin; under load the odd XCD of a pair delivers about 3 % less

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     kv_layerstack_workspace_bytes,
     kv_decode_set_worker_trace,
     kv_decode_set_xcd_skew,
+    kv_decode_set_l2_touch,
     kv_decode_fetch_probe,
     kv_decode_set_waves_per_cu,
     kv_decode_get_waves_per_cu,

@@ -42,6 +42,7 @@ class KVTensor(ctypes.Structure):
 EXPORTS = [
     "kv_decode_attn", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
     "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew", "kv_decode_fetch_probe",
+    "kv_decode_set_l2_touch",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_worker_range", "kv_worker_of_tile", "kv_profile_enable", "kv_profile_read",
 ]
@@ -224,6 +225,10 @@ def kv_decode_attn_kv8(q, k_cache, v_cache, block_tables, context_lens, out, sca
     _check(lib.kv_decode_attn_kv8(*[ctypes.byref(d) for d in descs], float(scale), float(k_scale), float(v_scale), int(num_kv_heads), int(block_size), int(prefetch_distance),
                                   ctypes.c_void_p(_stream_handle(stream))))
     return out
+
+
+def kv_decode_set_l2_touch(tiles: int):
+    _check(load_library().kv_decode_set_l2_touch(int(tiles)))
 
 
 def kv_decode_set_xcd_skew(per_1024: int):

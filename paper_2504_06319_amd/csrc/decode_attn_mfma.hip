@@ -116,8 +116,17 @@ struct Geo {
 // FETCH_ONLY: the same ranges, cursor and fetch stream with the arithmetic left out (nothing is read from LDS,
 // nothing is written): the memory system's rate for exactly this access pattern, the ceiling the kernel is
 // measured against.
-template <Elem E, int D, int BS, int PD, bool FETCH_ONLY = false>
-__global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
+//
+// TOUCH (with PD = 0 only): the paper's own mechanism, prefetch into L2 (Section 3.2), for comparison with the
+// LDS ring.  gfx950 has no prefetch instruction, and an ordinary load used as a touch would sit in the wave's
+// in-order return queue in front of the loads of the current tile, so the touching is done by a second wave of
+// the workgroup: it walks the same range and reads one dword of every 128-byte line of the tile pairs ahead of
+// the consumer wave, in groups of p.l2_touch tiles, never more than two groups ahead (the consumer publishes
+// its tile count in LDS; the toucher's only wait is on that count, the consumer never waits for the toucher).
+// The consumer runs the PD = 0 flow (fetch, wait, compute) and finds its lines in L2.
+template <Elem E, int D, int BS, int PD, bool FETCH_ONLY = false, bool TOUCH = false>
+__global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_kernel(AttnParams p) {
+    static_assert(!TOUCH || (PD == 0 && !FETCH_ONLY), "the L2 touch wave accompanies the flow without LDS look-ahead");
     using G_ = Geo<D>;
     constexpr int NS = PD + 1;                  // LDS stages of the wave
     constexpr int TPB = BS / kTileTokens;       // 16-token tiles per KV block
@@ -129,10 +138,11 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int worker = blockIdx.x;
-    const int lane = threadIdx.x;
+    const int lane = TOUCH ? threadIdx.x % kWaveSize : threadIdx.x;
+    const bool toucher = TOUCH && threadIdx.x >= kWaveSize;   // the second wave of a TOUCH workgroup
     const int lq = lane / 16, lr = lane % 16;   // lane group (0..3) and index in the group
     const int G = p.G, Hkv = p.Hkv;
-    const bool traced = p.worker_trace != nullptr;            // 100 MHz clock readings for the host, when asked for
+    const bool traced = p.worker_trace != nullptr && !toucher;   // 100 MHz clock readings for the host, when asked for
     const unsigned long long t_entry = traced ? wall_clock64() : 0;
     const int max_len = p.MB * BS;
     const_i32_ptr cl = (const_i32_ptr)p.context_lens;
@@ -171,6 +181,43 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         } while (c.ntiles == 0 && c.b + 1 < p.B);
     };
 
+    const unsigned char* kcache = reinterpret_cast<const unsigned char*>(p.k_cache);
+    const unsigned char* vcache = reinterpret_cast<const unsigned char*>(p.v_cache);
+    volatile uint32_t* progress = reinterpret_cast<volatile uint32_t*>(smem + NS * kStageBytes);   // TOUCH only
+    if constexpr (TOUCH) {
+        if (threadIdx.x == 0) *progress = 0;       // tiles the consumer has started
+        __syncthreads();
+        if (toucher) {
+            constexpr int kLines = kTileBytes / 128, kMaxGroup = 8;
+            const int group = min(max(p.l2_touch, 1), kMaxGroup);
+            const unsigned char* cache = lane < 32 ? kcache : vcache;       // lanes 0..31 touch K lines, 32..63 V lines
+            const int64_t sblk = lane < 32 ? p.kv_stride_blk : p.v_stride_blk, sh = lane < 32 ? p.kv_stride_h : p.v_stride_h;
+            Cursor ct = ca;
+            uint32_t acc = 0;
+            for (int64_t base = r0; base < r1; base += group) {
+                // stay at most two groups ahead of the consumer; it counts up to r1 - r0, so this wait ends
+                const uint32_t first = (uint32_t)(base - r0);
+                while (first >= *progress + 2u * (uint32_t)group) __builtin_amdgcn_s_sleep(4);
+                uint32_t v[kMaxGroup];
+#pragma unroll
+                for (int k = 0; k < kMaxGroup; ++k) {
+                    v[k] = 0;
+                    if (k < group && base + k < r1) {
+                        int phys = bt[(int64_t)ct.b * p.bt_stride_b + ct.j / TPB];
+                        phys = __builtin_amdgcn_readfirstlane(min(max(phys, 0), p.NBLK - 1));
+                        const unsigned char* tile = cache + ((int64_t)phys * sblk + (int64_t)ct.kvh * sh) * 2 + (ct.j % TPB) * kTileBytes;
+                        if (lane % 32 < kLines) v[k] = *reinterpret_cast<const uint32_t*>(tile + (lane % 32) * 128);
+                        if (base + k + 1 < r1) advance(ct);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < kMaxGroup; ++k) acc ^= v[k];
+            }
+            if (acc == 0x9e3779b9u && p.l2_touch < 0) p.partials[0] = 0.f;      // never true: keeps the loads alive
+            return;
+        }
+    }
+
     // ---- Q^T operand of a unit: lane (g = lr, lq) holds Q[g][(4j + lq) * 8 .. +8], zero rows for g >= G
     u32x4 qb[KJ];
     auto load_q = [&](int b, int kvh) {
@@ -208,8 +255,6 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
         vread[cb] = kTileBytes + vt * kRowBytes + (((2 * cb + (lane % 4) / 2) ^ G_::swz_v(vt)) << 4) + ((lane % 2) << 3);
 
     const uint32_t ring_addr = (uint32_t)(uintptr_t)KVP_LDS(smem);      // LDS byte address of the ring
-    const unsigned char* kcache = reinterpret_cast<const unsigned char*>(p.k_cache);
-    const unsigned char* vcache = reinterpret_cast<const unsigned char*>(p.v_cache);
 
     auto issue = [&](const Cursor& c, int stage) {   // asynchronous fetch of one K tile and one V tile into a stage
         int phys = bt[(int64_t)c.b * p.bt_stride_b + c.j / TPB];   // only entries of tiles inside the range are read
@@ -251,6 +296,9 @@ __global__ __launch_bounds__(kWaveSize) void attn_mfma_kernel(AttnParams p) {
     int piece_first_j = ca.j;                     // where the current piece of the current unit began
     bool piece_at_range_start = true;
     for (int64_t r = r0; r < r1; ++r) {
+        if constexpr (TOUCH) {
+            if (lane == 0) *progress = (uint32_t)(r - r0 + 1);
+        }
         if constexpr (PD == 0) {
             issue_next(0);
             wait_vmcnt<0>();
@@ -491,6 +539,28 @@ static int launch_fetch_pd(const AttnParams& p, hipStream_t stream) {
         case 4: return go(attn_mfma_kernel<Elem::BF16, D, BS, 4, true>, 4);
         default: return -1;
     }
+}
+
+template <Elem E, int D, int BS>
+static int launch_touch_variant(const AttnParams& p, hipStream_t stream) {
+    auto kern = attn_mfma_kernel<E, D, BS, 0, false, true>;
+    hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(2 * kWaveSize), (size_t)mfma_worker_lds_bytes(0, D) + 16, stream, p);
+    return 0;
+}
+
+// The attention kernel without LDS look-ahead, each worker accompanied by a wave that touches the tiles ahead
+// of it into L2 (p.l2_touch tiles per group).  Returns 0 or -1.
+int launch_attn_l2_touch(const AttnParams& p, int elem, int d, int bs, hipStream_t stream) {
+    if (p.num_workers < 1 || p.num_workers > kMaxMfmaWorkers || p.tile_shift != kTileShift) return -1;
+    if (p.prefetch_distance != 0 || p.l2_touch < 1 || p.l2_touch > 8) return -1;
+    if (d != 64 && d != 128) return -1;
+    if (bs != 16 && bs != 32) return -1;
+    if (elem == (int)Elem::F16) {
+        if (d == 128) return bs == 16 ? launch_touch_variant<Elem::F16, 128, 16>(p, stream) : launch_touch_variant<Elem::F16, 128, 32>(p, stream);
+        return bs == 16 ? launch_touch_variant<Elem::F16, 64, 16>(p, stream) : launch_touch_variant<Elem::F16, 64, 32>(p, stream);
+    }
+    if (d == 128) return bs == 16 ? launch_touch_variant<Elem::BF16, 128, 16>(p, stream) : launch_touch_variant<Elem::BF16, 128, 32>(p, stream);
+    return bs == 16 ? launch_touch_variant<Elem::BF16, 64, 16>(p, stream) : launch_touch_variant<Elem::BF16, 64, 32>(p, stream);
 }
 
 // The fetch stream of launch_attn_mfma without its arithmetic; writes nothing.  Returns 0 or -1.

@@ -29,6 +29,7 @@ size_t g_ws_bytes = 0;
 void* g_trace_ptr = nullptr;         // optional per-worker timestamps (under g_ws_mutex)
 size_t g_trace_bytes = 0;
 std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
+std::atomic<int> g_l2_touch{0};      // tiles per group of the L2 touch wave (0 = none); calls with prefetch_distance 0 only
 std::atomic<int> g_xcd_skew{20};     // per 1024: even workers get 1024 + 20 parts of the tile space, odd ones 1024 - 20
 constexpr int kMaxDevices = 64;
 std::atomic<int> g_num_cus[kMaxDevices];   // compute units per device ordinal, read once each (0 = not read yet)
@@ -178,6 +179,7 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     const int nw = cus * waves_per_cu(prefetch_distance, (int)d, kv8);
     p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
     p.xcd_skew = g_xcd_skew.load();
+    p.l2_touch = (!kv8 && prefetch_distance == 0) ? g_l2_touch.load() : 0;
     const size_t need = kvp::kGemmTicketBytes + kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     if (!g_ws_ptr || g_ws_bytes < need)
@@ -214,7 +216,10 @@ int run_attn(const Resolved& r, hipStream_t stream) {
     if (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity && (g_prof_seen++ % g_prof_every) == 0) slot = g_prof_calls++;
     prof_lock.unlock();
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), stream);
-    if ((r.kv8 ? kvp::launch_attn_kv8(r.p, r.elem, r.d, r.bs, stream) : kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, stream)) != 0)
+    const int launched = r.kv8          ? kvp::launch_attn_kv8(r.p, r.elem, r.d, r.bs, stream)
+                         : r.p.l2_touch ? kvp::launch_attn_l2_touch(r.p, r.elem, r.d, r.bs, stream)
+                                        : kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, stream);
+    if (launched != 0)
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);
@@ -415,6 +420,12 @@ int kv_decode_set_waves_per_cu(int waves) {
     if (waves < 0 || waves > kMaxWavesPerCU)
         return fail(KV_ERR_INVALID, "kv_decode_set_waves_per_cu: %d outside 0..%d", waves, kMaxWavesPerCU);
     g_waves_per_cu.store(waves);
+    return KV_OK;
+}
+
+int kv_decode_set_l2_touch(int tiles) {
+    if (tiles < 0 || tiles > 8) return fail(KV_ERR_INVALID, "kv_decode_set_l2_touch: %d outside 0..8", tiles);
+    g_l2_touch.store(tiles);
     return KV_OK;
 }
 

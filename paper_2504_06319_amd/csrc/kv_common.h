@@ -31,6 +31,7 @@ struct AttnParams {
     int32_t prefetch_distance;
     int32_t num_workers;      // persistent waves (workers) of the launch
     int32_t tile_shift;       // log2 of the tokens per tile of the flat tile space: 4 (16-bit caches) or 5 (8-bit)
+    int32_t l2_touch;         // > 0 with prefetch_distance 0: a second wave per worker touches this many tiles per group into L2
     int32_t xcd_skew;         // per-1024 skew of the range sizes between even and odd workers (XCDs)
     float scale_log2e;        // scale * log2(e) (* k_scale for an 8-bit cache): logits live in the base-2 domain
     float out_scale;          // multiplies every output row: 1, or v_scale for an 8-bit cache
@@ -51,6 +52,7 @@ __device__ __forceinline__ uint16_t pack1(float f) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
+int launch_attn_l2_touch(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_fetch_probe(const AttnParams& p, int d, int bs, hipStream_t stream);
 int launch_attn_kv8(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_finalize_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);

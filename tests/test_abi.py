@@ -172,6 +172,12 @@ def test_worker_trace_registration_arguments_are_checked():
     assert lib.kv_decode_set_worker_trace(ctypes.c_void_p(0x1004), 64) == 1
 
 
+def test_l2_touch_range_is_checked():
+    lib = kv.load_library()
+    assert lib.kv_decode_set_l2_touch(-1) == 1 and lib.kv_decode_set_l2_touch(9) == 1
+    assert lib.kv_decode_set_l2_touch(4) == 0 and lib.kv_decode_set_l2_touch(0) == 0
+
+
 def test_xcd_skew_range_is_checked():
     lib = kv.load_library()
     assert lib.kv_decode_set_xcd_skew(-1) == 1 and lib.kv_decode_set_xcd_skew(257) == 1

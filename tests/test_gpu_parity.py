@@ -293,6 +293,45 @@ def test_fetch_probe_runs_the_fetch_stream_and_writes_nothing(d, bs):
     check_case(c, 2, "attention after the probe")
 
 
+@pytest.mark.parametrize("d,bs", [(128, 16), (128, 32), (64, 16), (64, 32)])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_l2_touch_wave_changes_no_bit(d, bs, dtype):
+    """The comparison mode with a second wave per worker touching tiles into L2 ahead of it: the worker's own
+    arithmetic is that of prefetch_distance 0, so every group size gives the bits of the plain call."""
+    lens = [700, 0, 33, 1500, 16, 4000, 257, 1, 2048, 5]
+    c = synth.make_case(_cfg(8, 2, d, bs, dtype), 83, DEV, poison=True, lens=lens)
+    plain = run_hip(c, 0)
+    compare(plain, run_oracle(c), "plain")
+    try:
+        for tiles in (1, 3, 8):
+            kv.kv_decode_set_l2_touch(tiles)
+            got = run_hip(c, 0)
+            assert torch.equal(got.view(torch.int16), plain.view(torch.int16)), f"group of {tiles}"
+            # other distances ignore the setting
+            assert torch.equal(run_hip(c, 2).view(torch.int16), run_hip(c, 2).view(torch.int16))
+    finally:
+        kv.kv_decode_set_l2_touch(0)
+
+
+def test_l2_touch_wave_on_a_full_size_configuration():
+    cfg = synth.CONFIGS[1]
+    c = synth.make_case(cfg, synth.config_seed(1), DEV)
+    plain = run_hip(c, 0)
+    kv.kv_decode_set_l2_touch(4)
+    try:
+        for waves in (2, 6):
+            kv.kv_decode_set_waves_per_cu(waves)
+            ref = run_hip(c, 0) if waves != 6 else plain
+            kv.kv_decode_set_l2_touch(0)
+            ref = run_hip(c, 0)
+            kv.kv_decode_set_l2_touch(4)
+            got = run_hip(c, 0)
+            assert torch.equal(got.view(torch.int16), ref.view(torch.int16)), f"{waves} waves"
+    finally:
+        kv.kv_decode_set_l2_touch(0)
+        kv.kv_decode_set_waves_per_cu(0)
+
+
 def test_worker_timeline_accounts_for_every_tile():
     """Every worker reports its entry / range-located / exit clock readings and its tile count: the counts add
     up to the tiles of the batch (per kv head), the readings are ordered, and the result is unchanged."""
