@@ -119,7 +119,8 @@ __device__ __forceinline__ int wave_sum_i32(int v) {
 }
 
 // scan_total: per-kv-head tile total of the batch.  scan_locate: for a flat position `target`, the sequence
-// that holds it, i.e. the last b whose first flat tile Hkv * cum[b] is <= target, and that cum[b].
+// that holds it, i.e. the last b whose first flat tile Hkv * cum[b] is <= target, that cum[b] and the sequence's
+// clamped length (handed back from the scan's registers: one dependent memory round trip less at the start).
 
 __device__ __forceinline__ int scan_total(const_i32_ptr cl, int B, int max_len, int lane, int shift) {
     int total = 0;
@@ -132,11 +133,12 @@ __device__ __forceinline__ int scan_total(const_i32_ptr cl, int B, int max_len, 
 }
 
 __device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len, int lane, int shift, int Hkv,
-                                            int64_t target, int& b_out, int& cum_out) {
-    int cum = 0, found_b = 0, found_cum = 0;
+                                            int64_t target, int& b_out, int& cum_out, int& n_out) {
+    int cum = 0, found_b = 0, found_cum = 0, found_n = 0;
     for (int base = 0; base < B; base += kWaveSize) {
         const int idx = base + lane;
-        const int t = idx < B ? tiles_of(clamp_len(cl[idx], max_len), shift) : 0;
+        const int n = idx < B ? clamp_len(cl[idx], max_len) : 0;
+        const int t = tiles_of(n, shift);
         int incl = t;
 #pragma unroll
         for (int off = 1; off < kWaveSize; off <<= 1) {
@@ -149,11 +151,13 @@ __device__ __forceinline__ void scan_locate(const_i32_ptr cl, int B, int max_len
         if (cnt == 0) break;                       // the predicate is monotone: nothing further matches
         found_b = base + cnt - 1;
         found_cum = __builtin_amdgcn_readlane(excl, cnt - 1);
+        found_n = __builtin_amdgcn_readlane(n, cnt - 1);
         cum += __builtin_amdgcn_readlane(incl, kWaveSize - 1);
         if (cnt < kWaveSize) break;
     }
     b_out = found_b;
     cum_out = found_cum;
+    n_out = found_n;
 }
 
 // Range boundaries of the flat tile space.  Worker w's share is proportional to 1024 + skew for even w and

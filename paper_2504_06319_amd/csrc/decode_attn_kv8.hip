@@ -113,10 +113,10 @@ __global__ __launch_bounds__(kWaveSize) void attn_kv8_kernel(AttnParams p) {
     const int64_t r1 = range_start(worker + 1, T, nw, skew);
     Cursor ca;
     {
-        int b0, cum0;
-        scan_locate(cl, p.B, max_len, lane, kTileShift8, Hkv, r0, b0, cum0);
+        int b0, cum0, n0;
+        scan_locate(cl, p.B, max_len, lane, kTileShift8, Hkv, r0, b0, cum0, n0);
         ca.b = b0;
-        ca.n = clamp_len(cl[b0], max_len);
+        ca.n = n0;
         ca.ntiles = tiles_of(ca.n, kTileShift8);
         const int rem = (int)(r0 - (int64_t)Hkv * cum0);
         ca.kvh = rem / ca.ntiles;

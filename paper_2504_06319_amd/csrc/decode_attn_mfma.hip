@@ -160,10 +160,10 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
     const int64_t r1 = range_start(worker + 1, T, nw, skew);
     Cursor ca;
     {
-        int b0, cum0;
-        scan_locate(cl, p.B, max_len, lane, kTileShift, Hkv, r0, b0, cum0);
+        int b0, cum0, n0;
+        scan_locate(cl, p.B, max_len, lane, kTileShift, Hkv, r0, b0, cum0, n0);
         ca.b = b0;
-        ca.n = clamp_len(cl[b0], max_len);
+        ca.n = n0;
         ca.ntiles = tiles_of(ca.n, kTileShift);
         const int rem = (int)(r0 - (int64_t)Hkv * cum0);
         ca.kvh = rem / ca.ntiles;
@@ -616,9 +616,9 @@ __global__ __launch_bounds__(kWaveSize) void attn_touch_kernel(AttnParams p, int
     if (worker >= nw) return;
     const int skew = effective_skew(T, nw, p.xcd_skew);
     const int64_t r0 = range_start(worker, T, nw, skew), r1 = range_start(worker + 1, T, nw, skew);
-    int b0, cum0;
-    scan_locate(cl, p.B, max_len, lane, kTileShift, Hkv, r0, b0, cum0);
-    int b = b0, n = clamp_len(cl[b0], max_len), ntiles = tiles_of(n, kTileShift);
+    int b0, cum0, n0;
+    scan_locate(cl, p.B, max_len, lane, kTileShift, Hkv, r0, b0, cum0, n0);
+    int b = b0, n = n0, ntiles = tiles_of(n, kTileShift);
     const int rem = (int)(r0 - (int64_t)Hkv * cum0);
     int kvh = rem / ntiles, j = rem - kvh * ntiles;
     uint32_t acc = 0;
