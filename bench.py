@@ -246,6 +246,8 @@ def main():
     ap.add_argument("--l2-touch", type=int, default=0, metavar="TILES",
                     help="comparison mode: with --prefetch-distance 0, a second wave per worker touches this many tiles "
                          "per group into L2 ahead of it (the paper's mechanism in place of the LDS ring)")
+    ap.add_argument("--two-phase", action="store_true",
+                    help="comparison variant: the two-phase kernel form (all logits of a chunk, then the V tiles)")
     ap.add_argument("--fetch-ceiling", action="store_true",
                     help="time the attention kernel's fetch stream without its arithmetic beside the kernel itself "
                          "over a grid of occupancies and prefetch distances, print the table and exit")
@@ -272,6 +274,8 @@ def main():
         kv.kv_decode_set_waves_per_cu(args.waves_per_cu)
     if args.l2_touch:
         kv.kv_decode_set_l2_touch(args.l2_touch)
+    if args.two_phase:
+        kv.kv_decode_set_variant(kv.KV_VARIANT_TWO_PHASE)
 
     def make_cases(index, copies=2, kv8=False):
         cfg = synth.CONFIGS[index]
@@ -339,8 +343,10 @@ def main():
                    "head_dim": cfg["d"], "block_size": cfg["bs"],
                    "context_lens": "fixed" if "lens" in cfg else f"uniform{list(cfg['len_range'])}",
                    "kv_bytes_per_step": kvb, "prefetch_distance": pd_on,
-                   "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, cfg["d"]),
-                   **({"l2_touch_tiles": args.l2_touch} if args.l2_touch and pd_on == 0 and not args.kv8 else {})},
+                   "waves_per_cu": (kv.kv_decode_get_waves_per_cu_kv8(pd_on, cfg["d"]) if args.kv8 else
+                                    kv.kv_decode_get_waves_per_cu_for(pd_on, cfg["d"], cfg["Hq"] // cfg["Hkv"])),
+                   **({"l2_touch_tiles": args.l2_touch} if args.l2_touch and pd_on == 0 and not args.kv8 else {}),
+                   **({"variant": "two-phase"} if args.two_phase and not args.kv8 else {})},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "tokens_per_s": cfg["B"] / (ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

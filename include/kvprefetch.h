@@ -160,14 +160,32 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
  * Each worker holds (prefetch_distance + 1) stages of LDS (8 KB each at head_dim 128, 4 KB at
  * 64), so the number in effect is capped by the 160 KB of a compute unit (Eq. 2 re-derived
  * for LDS as the prefetch target: bytes in flight per CU = stage x prefetch_distance x waves);
- * kv_decode_get_waves_per_cu returns the number a call with that distance and head_dim would use.
+ * kv_decode_get_waves_per_cu returns the number a call with that distance and head_dim would use
+ * (for the kernel variant in effect, see kv_decode_set_variant).
  */
 int kv_decode_set_waves_per_cu(int waves);
 int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
+/* The same for a given number of query heads per kv head (1 .. 16), on which the LDS of a worker of the
+ * two-phase variant depends (kv_decode_get_waves_per_cu assumes 16 there); 0 for invalid arguments. */
+int kv_decode_get_waves_per_cu_for(int prefetch_distance, int head_dim, int q_heads_per_kv_head);
 /* The same for kv_decode_attn_kv8 (stages of the same bytes, holding 32 tokens; twice the arithmetic
  * per byte, so more waves: at head_dim 128 6 waves up to distance 2 and 4 beyond, at head_dim 64 12
  * waves at distance 0 and 8 beyond). */
 int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
+
+/*
+ * Kernel form of kv_decode_attn (and of the layer stack's attention) on 16-bit caches.
+ * KV_VARIANT_ONE_PASS (default): online softmax, the K and the V tile of 16 tokens fetched and
+ * consumed together.  KV_VARIANT_TWO_PHASE: the form of the kernel the paper patches (its Sections
+ * 3.1 and 3.2): per chunk of up to 512 tokens first all logits (next K tile prefetched during the
+ * current one's product), kept in LDS, then the weights applied to the V tiles (next V tile
+ * prefetched likewise); prefetch_distance d keeps 2 d single tiles in flight, the bytes of the
+ * one-pass form.  Same work mapping, workspace and results up to rounding; each worker holds
+ * (2 d + 1) tiles plus 32 KB of logits in LDS, which caps the waves per compute unit.
+ * kv_decode_attn_kv8 ignores the setting.
+ */
+enum { KV_VARIANT_ONE_PASS = 0, KV_VARIANT_TWO_PHASE = 1 };
+int kv_decode_set_variant(int variant);
 
 /*
  * Comparison mode: the paper's own mechanism, prefetch into L2 (its Section 3.2), in place of the
@@ -176,7 +194,8 @@ int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
  * ahead of it into L2 (one dword per 128-byte line), in groups of `tiles` tiles and at most two
  * groups ahead of the worker; the worker itself fetches, waits and computes as at distance 0 and
  * finds its lines in L2.  Results are those of distance 0.  0 (the default) switches it off;
- * 0 .. 8.  Calls with another prefetch_distance and kv_decode_attn_kv8 ignore it.
+ * 0 .. 8.  Calls with another prefetch_distance, the two-phase variant and kv_decode_attn_kv8
+ * ignore it.
  */
 int kv_decode_set_l2_touch(int tiles);
 

@@ -15,6 +15,10 @@ from .binding import (  # noqa: F401
     kv_decode_set_worker_trace,
     kv_decode_set_xcd_skew,
     kv_decode_set_l2_touch,
+    kv_decode_set_variant,
+    kv_decode_get_waves_per_cu_for,
+    KV_VARIANT_ONE_PASS,
+    KV_VARIANT_TWO_PHASE,
     kv_decode_fetch_probe,
     kv_decode_set_waves_per_cu,
     kv_decode_get_waves_per_cu,

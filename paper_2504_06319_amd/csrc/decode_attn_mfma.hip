@@ -43,76 +43,6 @@
 namespace kvp {
 
 
-// LDS reads of the ring are written as inline assembly on purpose.  The compiler knows
-// that global_load_lds writes LDS and, unable to tell ring stages apart, would put a
-// wait for ALL outstanding fetches in front of every LDS read it can see, which would
-// serialise the look-ahead.  The fetch completion is tracked by hand instead (vmcnt),
-// and so is the completion of these reads (lgkmcnt, LDS returns data in order).
-__device__ __forceinline__ void lds_read_b128_x4(u32x4& r0, u32x4& r1, u32x4& r2, u32x4& r3,
-                                                 uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3) {
-    asm volatile(
-        "ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7"
-        : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
-        : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
-        : "memory");
-}
-
-__device__ __forceinline__ void lds_read_tr16_x4(u32x2& r0, u32x2& r1, u32x2& r2, u32x2& r3,
-                                                 uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3) {
-    asm volatile(
-        "ds_read_b64_tr_b16 %0, %4\n\tds_read_b64_tr_b16 %1, %5\n\tds_read_b64_tr_b16 %2, %6\n\tds_read_b64_tr_b16 %3, %7"
-        : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
-        : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
-        : "memory");
-}
-
-__device__ __forceinline__ void lds_read_b128_x2(u32x4& r0, u32x4& r1, uint32_t a0, uint32_t a1) {
-    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3" : "=&v"(r0), "=&v"(r1) : "v"(a0), "v"(a1) : "memory");
-}
-
-// Wait until at most N of this wave's LDS operations are outstanding; the registers are
-// passed through so that no use of them can be scheduled above the wait.
-template <int N>
-__device__ __forceinline__ void lds_wait_k(u32x4& r0, u32x4& r1, u32x4& r2, u32x4& r3) {
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3) : "n"(N) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void lds_wait_k(u32x4& r0, u32x4& r1) {
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(r0), "+v"(r1) : "n"(N) : "memory");
-}
-__device__ __forceinline__ void lds_wait_v(u32x2 (&r)[4]) {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) : : "memory");
-}
-__device__ __forceinline__ void lds_wait_v(u32x2 (&r)[8]) {
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
-                 :
-                 : "memory");
-}
-
-
-constexpr int kTileTokens = 16;
-constexpr int kTileShift = 4;
-
-// Per-head_dim geometry of a 16-token tile.
-template <int D>
-struct Geo {
-    static constexpr int kRowBytes = D * 2;                        // one token's row of K (or V)
-    static constexpr int kTileBytes = kTileTokens * kRowBytes;     // 4 KB (d 128) / 2 KB (d 64) for K, the same for V
-    static constexpr int kStageBytes = 2 * kTileBytes;
-    static constexpr int kChunks = D / 8;                          // 16-byte chunks per row
-    static constexpr int kRowsPerLoad = kWaveSize / kChunks;       // rows one wave-wide 1 KB fetch lands
-    static constexpr int kLoadsPerTile = kTileTokens / kRowsPerLoad;
-    static constexpr int kSwzShift = 16 / kChunks;                 // rows that share a swizzle value
-    static constexpr int kKSteps = D / 32;                         // MFMAs of the logits
-    static constexpr int kColBlocks = D / 16;                      // 16-column blocks of the output
-    static constexpr int kPartialStride = D + 4;                   // floats per partial row: acc, max, sum, 2 pad (16-byte rows)
-    __host__ __device__ static constexpr int swz_k(int row) { return (row / kSwzShift) % kChunks; }
-    // V swizzle of the 16-byte chunk index: even, so that it moves the 32-byte block a transpose read takes
-    __host__ __device__ static constexpr int swz_v(int row) { return 2 * ((row / kSwzShift) % (kChunks / 2)); }
-};
-
-
 // FETCH_ONLY: the same ranges, cursor and fetch stream with the arithmetic left out (nothing is read from LDS,
 // nothing is written): the memory system's rate for exactly this access pattern, the ceiling the kernel is
 // measured against.

@@ -29,6 +29,7 @@ size_t g_ws_bytes = 0;
 void* g_trace_ptr = nullptr;         // optional per-worker timestamps (under g_ws_mutex)
 size_t g_trace_bytes = 0;
 std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
+std::atomic<int> g_variant{KV_VARIANT_ONE_PASS};   // kernel form of kv_decode_attn on 16-bit caches
 std::atomic<int> g_l2_touch{0};      // tiles per group of the L2 touch wave (0 = none); calls with prefetch_distance 0 only
 std::atomic<int> g_xcd_skew{20};     // per 1024: even workers get 1024 + 20 parts of the tile space, odd ones 1024 - 20
 constexpr int kMaxDevices = 64;
@@ -58,12 +59,16 @@ int num_cus() {     // of the current device
 // arithmetic per byte (the widening included): two waves cannot keep up (measured 120 us against 90 us with six
 // on the Llama-3-8B-shaped batch), so it runs six waves (head_dim 128) or eight to twelve (head_dim 64) at every
 // distance the LDS allows, and four where five would fit (an odd count, uneven over the four SIMDs, is 40 %
-// slower).  Always capped by the LDS the rings need.
-int waves_per_cu(int prefetch_distance, int d, bool kv8) {
-    const int lds_limit = kLdsBytesPerCU / kvp::mfma_worker_lds_bytes(prefetch_distance, d);
+// slower).  The two-phase variant moves one tile per step where the one-pass kernel moves a pair, so it wants
+// twice the waves for the same bytes in flight (measured best: 12 / 6 / 4 at distance 0 / 1 / 2).  Always capped
+// by the LDS the rings (and the two-phase variant's logits buffer) need.
+int waves_per_cu(int prefetch_distance, int d, bool kv8, int two_phase_group = 0) {
+    const int lds_limit = kLdsBytesPerCU / (two_phase_group ? kvp::twophase_worker_lds_bytes(prefetch_distance, d, two_phase_group)
+                                                            : kvp::mfma_worker_lds_bytes(prefetch_distance, d));
     int w = g_waves_per_cu.load();
     if (w <= 0) {
-        if (kv8) w = d == 128 ? (prefetch_distance <= 2 ? 6 : 4) : (prefetch_distance == 0 ? 12 : 8);
+        if (two_phase_group) w = prefetch_distance == 0 ? 12 : prefetch_distance == 1 ? 6 : 4;
+        else if (kv8) w = d == 128 ? (prefetch_distance <= 2 ? 6 : 4) : (prefetch_distance == 0 ? 12 : 8);
         else if (d == 128) w = prefetch_distance <= 1 ? 6 : 2;
         else w = prefetch_distance <= 1 ? 8 : 4;
     }
@@ -89,7 +94,7 @@ bool dense_tile(const kv_tensor* t) {   // [NBLK, Hkv, bs, d] with the [bs, d] t
 struct Resolved {
     kvp::AttnParams p;
     int elem, d, bs;
-    bool kv8;
+    bool kv8, two_phase;
 };
 
 int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
@@ -174,12 +179,13 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.scale_log2e = scale * kvp::kLog2e * (kv8 ? k_scale : 1.0f);
     p.out_scale = kv8 ? v_scale : 1.0f;
     r->elem = q->dtype; r->d = (int)d; r->bs = block_size; r->kv8 = kv8;
+    r->two_phase = !kv8 && g_variant.load() == KV_VARIANT_TWO_PHASE;
     const int cus = num_cus();
     if (cus <= 0) return fail(KV_ERR_HIP, "kv_decode_attn: cannot read the device's compute unit count");
-    const int nw = cus * waves_per_cu(prefetch_distance, (int)d, kv8);
+    const int nw = cus * waves_per_cu(prefetch_distance, (int)d, kv8, r->two_phase ? G : 0);
     p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
     p.xcd_skew = g_xcd_skew.load();
-    p.l2_touch = (!kv8 && prefetch_distance == 0) ? g_l2_touch.load() : 0;
+    p.l2_touch = (!kv8 && !r->two_phase && prefetch_distance == 0) ? g_l2_touch.load() : 0;
     const size_t need = kvp::kGemmTicketBytes + kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     if (!g_ws_ptr || g_ws_bytes < need)
@@ -217,6 +223,7 @@ int run_attn(const Resolved& r, hipStream_t stream) {
     prof_lock.unlock();
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 0), stream);
     const int launched = r.kv8          ? kvp::launch_attn_kv8(r.p, r.elem, r.d, r.bs, stream)
+                         : r.two_phase  ? kvp::launch_attn_twophase(r.p, r.elem, r.d, r.bs, stream)
                          : r.p.l2_touch ? kvp::launch_attn_l2_touch(r.p, r.elem, r.d, r.bs, stream)
                                         : kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, stream);
     if (launched != 0)
@@ -423,6 +430,13 @@ int kv_decode_set_waves_per_cu(int waves) {
     return KV_OK;
 }
 
+int kv_decode_set_variant(int variant) {
+    if (variant != KV_VARIANT_ONE_PASS && variant != KV_VARIANT_TWO_PHASE)
+        return fail(KV_ERR_INVALID, "kv_decode_set_variant: unknown variant %d", variant);
+    g_variant.store(variant);
+    return KV_OK;
+}
+
 int kv_decode_set_l2_touch(int tiles) {
     if (tiles < 0 || tiles > 8) return fail(KV_ERR_INVALID, "kv_decode_set_l2_touch: %d outside 0..8", tiles);
     g_l2_touch.store(tiles);
@@ -438,7 +452,15 @@ int kv_decode_set_xcd_skew(int per_1024) {
 
 int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim) {
     if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE || (head_dim != 64 && head_dim != 128)) return 0;
-    return waves_per_cu(prefetch_distance, head_dim, false);
+    // (two-phase variant: for the widest group of query heads, 16, whose logits buffer is the largest)
+    return waves_per_cu(prefetch_distance, head_dim, false, g_variant.load() == KV_VARIANT_TWO_PHASE ? 16 : 0);
+}
+
+int kv_decode_get_waves_per_cu_for(int prefetch_distance, int head_dim, int q_heads_per_kv_head) {
+    if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE || (head_dim != 64 && head_dim != 128) ||
+        q_heads_per_kv_head < 1 || q_heads_per_kv_head > 16)
+        return 0;
+    return waves_per_cu(prefetch_distance, head_dim, false, g_variant.load() == KV_VARIANT_TWO_PHASE ? q_heads_per_kv_head : 0);
 }
 
 int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim) {

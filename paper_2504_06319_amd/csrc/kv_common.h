@@ -52,6 +52,8 @@ __device__ __forceinline__ uint16_t pack1(float f) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 int launch_attn_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
+int launch_attn_twophase(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
+int twophase_worker_lds_bytes(int prefetch_distance, int d, int G);
 int launch_attn_l2_touch(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);
 int launch_fetch_probe(const AttnParams& p, int d, int bs, hipStream_t stream);
 int launch_attn_kv8(const AttnParams& p, int elem, int d, int bs, hipStream_t stream);

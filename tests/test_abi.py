@@ -172,6 +172,21 @@ def test_worker_trace_registration_arguments_are_checked():
     assert lib.kv_decode_set_worker_trace(ctypes.c_void_p(0x1004), 64) == 1
 
 
+def test_variant_switch_and_its_occupancy():
+    lib = kv.load_library()
+    assert lib.kv_decode_set_variant(2) == 1 and lib.kv_decode_set_variant(-1) == 1
+    try:
+        kv.kv_decode_set_variant(kv.KV_VARIANT_TWO_PHASE)
+        # a worker holds 2 d + 1 tiles of 4 KB (head_dim 128) and 32 x G x 64 bytes of logits
+        assert [kv.kv_decode_get_waves_per_cu_for(d, 128, 4) for d in range(5)] == [12, 6, 4, 4, 3]
+        assert [kv.kv_decode_get_waves_per_cu_for(d, 128, 16) for d in range(5)] == [4, 3, 3, 2, 2]
+        assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [4, 3, 3, 2, 2]
+        assert kv.kv_decode_get_waves_per_cu_for(0, 128, 17) == 0 and kv.kv_decode_get_waves_per_cu_for(0, 96, 4) == 0
+    finally:
+        kv.kv_decode_set_variant(kv.KV_VARIANT_ONE_PASS)
+    assert [kv.kv_decode_get_waves_per_cu_for(d, 128, 4) for d in range(5)] == [6, 6, 2, 2, 2]
+
+
 def test_l2_touch_range_is_checked():
     lib = kv.load_library()
     assert lib.kv_decode_set_l2_touch(-1) == 1 and lib.kv_decode_set_l2_touch(9) == 1
