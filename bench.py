@@ -23,9 +23,34 @@ def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
+_EVENT_OVERHEAD_MS = None
+
+
+def event_bracket_overhead(torch, pairs=200):
+    """What a pair of HIP events costs by itself: the median time between two events recorded back to back on
+    the launch stream with nothing between them (about 5 us on this chip).  A bracket around a kernel reads
+    that much more than the kernel's own duration, so it is subtracted from every event-based kernel time."""
+    global _EVENT_OVERHEAD_MS
+    if _EVENT_OVERHEAD_MS is None:
+        def pair():
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            b.record()
+            return a, b
+        for _ in range(10):
+            pair()
+        torch.cuda.synchronize()
+        ps = [pair() for _ in range(pairs)]
+        torch.cuda.synchronize()
+        _EVENT_OVERHEAD_MS = sorted(a.elapsed_time(b) for a, b in ps)[pairs // 2]
+    return _EVENT_OVERHEAD_MS
+
+
 def timed_steps(kv, torch, cases, pd, steps, warmup):
     """W untimed + K timed steps, alternating between the cache copies.  Returns
-    (ms per step by wall clock, main-kernel ms per launch by HIP events on the launch stream)."""
+    (ms per step by wall clock, main-kernel ms per launch by HIP events on the launch stream, less what an
+    empty event bracket reads)."""
+    overhead = event_bracket_overhead(torch)
     def step(i):
         c = cases[i % len(cases)]
         if "k_scale" in c:                       # 8-bit cache
@@ -47,7 +72,7 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
     main_ms, n = kv.kv_profile_read()
     kv.kv_profile_enable(0, 1)
     assert n == (steps + every - 1) // every
-    return (t1 - t0) * 1e3 / steps, main_ms / n
+    return (t1 - t0) * 1e3 / steps, main_ms / n - overhead
 
 
 def layer_stack(kv, torch, synth, dev, steps, warmup, pd, cross, layers=None):
@@ -352,6 +377,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "attn_mfma_kernel (main attention kernel)", "kernel_ms": main_ms,
+                     "kernel_ms_event_bracket": main_ms + event_bracket_overhead(torch),
+                     "event_bracket_overhead_ms": event_bracket_overhead(torch),
                      "algorithmic_bytes_per_launch": kvb},
     }
     log(f"[bench] on: {ms:.4f} ms/step, {value:.0f} GB/s; main kernel {main_ms:.4f} ms")
