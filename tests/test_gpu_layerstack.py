@@ -70,6 +70,28 @@ def test_small_stack_matches_oracle(B, cross, layout, K):
             compare(outs[l], want_q, f"layer {l} on the GPU's own queries")
 
 
+@pytest.mark.parametrize("mode", ["two_phase", "l2_touch"])
+def test_stack_under_the_comparison_modes(mode):
+    """The layer stack's attention follows the kernel-form switch and the L2 touch mode."""
+    L, B, Hq, Hkv, d, bs, K, N = 2, 16, 8, 2, 128, 16, 128, 128
+    lens = [100 + 137 * i for i in range(B)]
+    cfg, layers, x, ws, y, outs = _stack(L, B, Hq, Hkv, d, bs, K, N, lens, 69)
+    try:
+        if mode == "two_phase":
+            kv.kv_decode_set_variant(kv.KV_VARIANT_TWO_PHASE)
+            _run(layers, x, ws, y, outs, q=[c["q"] for c in layers], pd=2, cross=1)
+        else:
+            kv.kv_decode_set_l2_touch(2)
+            _run(layers, x, ws, y, outs, q=[c["q"] for c in layers], pd=0)
+    finally:
+        kv.kv_decode_set_variant(kv.KV_VARIANT_ONE_PASS)
+        kv.kv_decode_set_l2_touch(0)
+    for l, c in enumerate(layers):
+        want = oracle.paged_attention(oracle.bits_of(c["q"]), oracle.bits_of(c["k_cache"]), oracle.bits_of(c["v_cache"]),
+                                      c["block_tables"].cpu().numpy(), c["context_lens"].cpu().numpy(), c["scale"], "bf16")
+        compare(outs[l], want, f"{mode}, layer {l}")
+
+
 def test_explicit_queries_bypass_the_gemm_output():
     L, B, Hq, Hkv, d, bs, K, N = 2, 16, 8, 2, 128, 16, 128, 128
     lens = [100 + 37 * i for i in range(B)]
