@@ -105,3 +105,52 @@ def test_one_pass_and_two_phase_agree_to_rounding():
     kv.kv_decode_set_variant(kv.KV_VARIANT_ONE_PASS)
     one = run_hip(c, 2).float()
     assert (one - two).abs().max() <= 2e-2
+
+
+def test_large_lds_launch_and_graph_capture():
+    """G = 16 at prefetch distance 4 needs 68 KB of LDS per worker (beyond the default limit of dynamic LDS, which
+    the launch raises once), and the comparison modes enqueue only kernels, so a stream capture records them:
+    the two-phase call and a call with the L2 touch wave are captured (eager warm-up first) and every replay must
+    equal the eager result bit for bit."""
+    cfg = _cfg(32, 2, 128, 16, "bf16")
+    lens = [900, 0, 17, 2500, 64, 1]
+    a = synth.make_case(cfg, 251, DEV, poison=True, lens=lens)
+    out, out_t = torch.empty_like(a["q"]), torch.empty_like(a["q"])
+
+    def enqueue(o2, ot):
+        kv.kv_decode_set_variant(kv.KV_VARIANT_TWO_PHASE)
+        run_args = (a["q"], a["k_cache"], a["v_cache"], a["block_tables"], a["context_lens"])
+        kv.kv_decode_attn(*run_args, o2, a["scale"], a["num_kv_heads"], a["block_size"], 4)
+        kv.kv_decode_set_variant(kv.KV_VARIANT_ONE_PASS)
+        kv.kv_decode_set_l2_touch(2)
+        kv.kv_decode_attn(*run_args, ot, a["scale"], a["num_kv_heads"], a["block_size"], 0)
+        kv.kv_decode_set_l2_touch(0)
+
+    try:
+        enqueue(out, out_t)
+        torch.cuda.synchronize()
+        compare(out, run_oracle(a), "eager, 68 KB of LDS per worker")
+        compare(out_t, run_oracle(a), "eager, L2 touch wave")
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                enqueue(out, out_t)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            b = synth.make_case(cfg, 251, DEV, poison=True, lens=lens, data_seed=400 + rep)
+            for key in ("q", "k_cache", "v_cache"):
+                a[key].copy_(b[key])
+            want, want_t = torch.empty_like(out), torch.empty_like(out)
+            enqueue(want, want_t)
+            torch.cuda.synchronize()
+            out.fill_(float("nan"))
+            out_t.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), want.view(torch.int16)), f"replay {rep}, two-phase"
+            assert torch.equal(out_t.view(torch.int16), want_t.view(torch.int16)), f"replay {rep}, L2 touch"
+        compare(out, run_oracle(a), "last replay")
+    finally:
+        kv.kv_decode_set_l2_touch(0)
