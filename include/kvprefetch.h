@@ -14,6 +14,12 @@
  * All tensor arguments are DEVICE memory owned by the caller.  The library
  * enqueues kernels on `stream` and returns without synchronising; it allocates
  * nothing and keeps no pointer after return except the registered workspace.
+ * State is kept per device (the device current at the call): workspace, the slices
+ * of it that streams hold, the side stream of the layer stack.  The tuning and
+ * comparison switches (kv_decode_set_waves_per_cu, _variant, _l2_touch, _xcd_skew)
+ * and the two measurement aids (kv_profile_*, kv_decode_set_worker_trace) are
+ * process-wide: they exist for benchmarks and tests, and a value set by one caller
+ * is seen by every later call.
  *
  * Every entry point returns a kv_status; kv_last_error() gives the text of the
  * last failure on the calling thread.  No C++ exception crosses this boundary.
@@ -108,10 +114,13 @@ int kv_decode_attn_kv8(const kv_tensor* q, const kv_tensor* k_cache, const kv_te
  *     q_l    = y[:, 0 : Hq*d] viewed [B, Hq, d]  (or q[l] when q != NULL: then y is unused by attention)
  *     outs[l] = kv_decode_attn(q_l, k_caches[l], v_caches[l], block_tables, context_lens, ...)
  * The GEMM is the compute window between two attention calls.  With
- * cross_layer_prefetch = 1 the leading KV tiles of layer l+1 are touched while
- * GEMM_l runs so they sit in the memory-side cache when attention_{l+1} starts;
- * results do not depend on it.  The paper prefetches only inside the attention kernel
- * (next iteration, Section 3.1); the cross-layer form is this repository's harness.
+ * cross_layer_prefetch = 1 the leading KV tiles of layer l (the first tiles of every
+ * worker's range) are touched on a side stream while GEMM_l, the kernel between
+ * attention_{l-1} and attention_l, runs, so they sit in the memory-side cache when
+ * attention_l starts; results do not depend on it.  The paper prefetches only inside
+ * the attention kernel (next iteration, Section 3.1); the cross-layer form is this
+ * repository's harness.  Every layer's arguments are checked before the first kernel is
+ * enqueued: a call that returns an error has enqueued nothing.
  *
  *   x        [B, K] bf16, rows dense;  gemm_out [B, N] bf16, rows dense, N >= Hq*d when q == NULL
  *   weights[l] bf16, one of
@@ -135,10 +144,12 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
 /*
  * Split-KV workspace (the block index range [s, e) that Algorithm 1 takes as input lets a
  * worker own part of a sequence; the pieces of a sequence that several workers share are
- * merged by a second kernel).  Bytes a call with these extents needs: a fixed bound, 4096 bytes
- * of words the dense layer of the layer stack uses, then two partial pieces of min(Hq, 16) rows
- * of (d + 4) floats for each of at most 4096 workers (69 MB at d 128, Hq >= 16).  0 for
- * unsupported extents.
+ * merged by a second kernel).  Bytes that are enough for any one call with these extents: a
+ * fixed bound, 4096 bytes of words the dense layer of the layer stack uses, then two partial
+ * pieces of min(Hq, 16) rows of (d + 4) floats for each of at most 4096 workers (69 MB at d 128,
+ * Hq >= 16).  0 for unsupported extents.  What a call really takes is two pieces of Hq/Hkv rows
+ * for each of its workers (compute units x waves per compute unit): 2 MB for 32 / 8 heads at
+ * two waves on 256 compute units.
  * kv_layerstack_workspace_bytes: what kv_decode_layerstack needs when weights are in operand
  * order: the same plus two fp32 partial tiles of 128 x 128 per 128 columns of the dense layer
  * (its two halves of K meet there); gemm_n = columns of the dense layer.
@@ -147,9 +158,16 @@ size_t kv_decode_workspace_bytes(int B, int Hq, int d, int max_context, int bloc
 size_t kv_layerstack_workspace_bytes(int num_q_heads, int head_dim, int gemm_n);
 
 /*
- * Register caller-owned device scratch used by later calls (any thread).  NULL/0 unregisters.
- * While registered the memory belongs to the library; calls that overlap in time on one
- * device share it and race.
+ * Register caller-owned device scratch for later calls on the CURRENT device (any thread;
+ * one registration per device).  NULL/0 unregisters.  While registered the memory belongs to the
+ * library, which hands it out in slices: the first call on a stream takes a slice of the size it
+ * needs from the unused end, later calls on that stream reuse it (or take a larger one), so
+ * calls enqueued on different streams never share scratch and may overlap in time.  A call that
+ * finds too little left returns KV_ERR_WORKSPACE and enqueues nothing; registering (the same or
+ * another buffer) releases every slice, which is only safe once earlier calls have completed.
+ * Calls on ONE stream share their slice, in stream order; a captured graph keeps the slice of
+ * the stream it was captured on, so replays of it must not overlap each other or other work of
+ * that stream.
  */
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
 

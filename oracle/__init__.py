@@ -16,4 +16,4 @@ from .paged_attention import (  # noqa: F401
 )
 from .layerstack import layer_gemm_bf16, round_to_bf16_bits, layerstack_layer  # noqa: F401
 from .working_set import block_bytes, iteration_working_set_bytes, max_resident_batches  # noqa: F401
-from .alg1_model import alg1_trace  # noqa: F401
+from .alg1_model import blocks_used, fetches_in_flight  # noqa: F401

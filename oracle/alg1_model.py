@@ -1,28 +1,24 @@
-"""Index model of the paper's Algorithm 1 (prefetching K blocks), one warp's view.
+"""Which KV blocks one warp uses and which it fetches ahead (paper, Algorithm 1), as sets.
 
-TEST INFRASTRUCTURE ONLY.  The algorithm walks block indices of a range [s, e) with a
-stride equal to the number of warps w; before computing on the current block it issues
-a prefetch of the block the same warp will reach on its next iteration, but only when
-that index is still inside the range.  The printed algorithm starts at s; here the warp
-with rank r starts at s + r so that the w warps of a thread block cover the range
-between them (reading noted in the design document).
+TEST INFRASTRUCTURE ONLY.  Stated as properties rather than as a program: of a block range
+[first, end) shared by ``warps`` warps, the warp of rank r uses the blocks whose offset from
+``first`` is congruent to r modulo ``warps``, in increasing order; while it computes on the
+i-th of them, the fetch of the (i + distance)-th is in flight, if the warp has that many.  The
+paper's algorithm is distance 1; distance 0 is its baseline (nothing is fetched ahead).
+Nothing outside the range is ever named, so no block-table entry at or past ``end`` is read.
 """
 
 
-def alg1_trace(s: int, e: int, w: int, rank: int = 0, distance: int = 1):
-    """Return (lookups, loads, prefetches) in program order for one warp.
+def blocks_used(first: int, end: int, warps: int, rank: int) -> list:
+    """Blocks the warp of this rank computes on, in the order it reaches them."""
+    return [i for i in range(first, end) if (i - first) % warps == rank]
 
-    ``distance`` generalises "next iteration" to "k iterations ahead" (the paper is
-    distance 1); distance 0 issues no prefetch at all.
-    """
-    lookups, loads, prefetches = [], [], []
-    block_idx = s + rank
-    while block_idx < e:
-        lookups.append(block_idx)          # bt[block_idx] -> k_ptr
-        loads.append(block_idx)            # K block -> registers
-        ahead = block_idx + distance * w
-        if distance > 0 and ahead < e:     # guard: nothing at or past e is touched
-            lookups.append(ahead)          # bt[block_idx + w] -> next_k_ptr
-            prefetches.append(ahead)
-        block_idx += w                     # (compute QK^T happens here)
-    return lookups, loads, prefetches
+
+def fetches_in_flight(first: int, end: int, warps: int, rank: int, distance: int) -> dict:
+    """For every block the warp computes on: the block whose fetch overlaps that computation, or None."""
+    used = blocks_used(first, end, warps, rank)
+    ahead = {}
+    for position, block in enumerate(used):
+        target = position + distance
+        ahead[block] = used[target] if 0 < distance and target < len(used) else None
+    return ahead

@@ -140,23 +140,41 @@ def _stream_handle(stream) -> int:
 
 
 _workspaces: dict = {}
-_registered = (0, 0)
+_registered: dict = {}          # device index -> (pointer, bytes) the library holds for that device
 
 
 def _ensure_workspace(device: torch.device, nbytes: int):
-    """Keep a torch-owned scratch buffer per device registered with the library."""
-    global _registered
+    """Keep a torch-owned scratch buffer per device registered with the library (which keeps one per device and
+    hands every calling stream its own slice): four times what one call can need, so that several streams fit."""
     lib = load_library()
     if nbytes == 0:
         return
-    key = (device.type, device.index)
-    ws = _workspaces.get(key)
+    index = device.index if device.index is not None else torch.cuda.current_device()
+    ws = _workspaces.get(index)
     if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
-        _workspaces[key] = ws
-    if _registered != (ws.data_ptr(), ws.numel()):
-        _check(lib.kv_decode_set_workspace(ctypes.c_void_p(ws.data_ptr()), ws.numel()))
-        _registered = (ws.data_ptr(), ws.numel())
+        if ws is not None:
+            torch.cuda.synchronize(index)        # registering again releases the slices earlier calls may still use
+        ws = torch.empty(max(4 * nbytes, 1 << 20), dtype=torch.uint8, device=device)
+        _workspaces[index] = ws
+    if _registered.get(index) != (ws.data_ptr(), ws.numel()):
+        with torch.cuda.device(index):
+            _check(lib.kv_decode_set_workspace(ctypes.c_void_p(ws.data_ptr()), ws.numel()))
+        _registered[index] = (ws.data_ptr(), ws.numel())
+
+
+def _call(fn, device: torch.device):
+    """Run a library call that takes a slice of the workspace.  When the workspace is used up by the slices of
+    other streams (status 4), wait for the device, release every slice by registering the buffer again and try
+    once more; not under a stream capture, where nothing may wait."""
+    status = fn()
+    index = device.index if device.index is not None else torch.cuda.current_device()
+    ws = _workspaces.get(index)
+    if status == 4 and ws is not None and not torch.cuda.is_current_stream_capturing():
+        torch.cuda.synchronize(index)
+        with torch.cuda.device(index):
+            _check(load_library().kv_decode_set_workspace(ctypes.c_void_p(ws.data_ptr()), ws.numel()))
+        status = fn()
+    _check(status)
 
 
 def kv_decode_workspace_bytes(B: int, Hq: int, d: int, max_context: int, block_size: int) -> int:
@@ -195,8 +213,8 @@ def kv_decode_attn(q, k_cache, v_cache, block_tables, context_lens, out, scale, 
                                          block_tables.shape[1] * block_size, block_size)
         _ensure_workspace(q.device, need)
     descs = [describe(t) for t in (q, k_cache, v_cache, block_tables, context_lens, out)]
-    _check(lib.kv_decode_attn(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
-                              int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))))
+    _call(lambda: lib.kv_decode_attn(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
+                                     int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))), q.device)
     return out
 
 
@@ -208,8 +226,8 @@ def kv_decode_fetch_probe(q, k_cache, v_cache, block_tables, context_lens, out, 
                                      block_tables.shape[1] * block_size, block_size)
     _ensure_workspace(q.device, need)
     descs = [describe(t) for t in (q, k_cache, v_cache, block_tables, context_lens, out)]
-    _check(lib.kv_decode_fetch_probe(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
-                                     int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))))
+    _call(lambda: lib.kv_decode_fetch_probe(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads), int(block_size),
+                                            int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))), q.device)
 
 
 def kv_decode_attn_kv8(q, k_cache, v_cache, block_tables, context_lens, out, scale, k_scale, v_scale,
@@ -222,8 +240,9 @@ def kv_decode_attn_kv8(q, k_cache, v_cache, block_tables, context_lens, out, sca
         _ensure_workspace(q.device, need)
     caches = [c.view(torch.float8_e4m3fn) if c.dtype == torch.uint8 else c for c in (k_cache, v_cache)]
     descs = [describe(t) for t in (q, caches[0], caches[1], block_tables, context_lens, out)]
-    _check(lib.kv_decode_attn_kv8(*[ctypes.byref(d) for d in descs], float(scale), float(k_scale), float(v_scale), int(num_kv_heads), int(block_size), int(prefetch_distance),
-                                  ctypes.c_void_p(_stream_handle(stream))))
+    _call(lambda: lib.kv_decode_attn_kv8(*[ctypes.byref(d) for d in descs], float(scale), float(k_scale), float(v_scale),
+                                         int(num_kv_heads), int(block_size), int(prefetch_distance),
+                                         ctypes.c_void_p(_stream_handle(stream))), q.device)
     return out
 
 
@@ -277,10 +296,10 @@ def kv_decode_layerstack(x, weights, gemm_out, q, k_caches, v_caches, block_tabl
     else:
         q_arr, q_keep = None, None
     dx, dg, dbt, dcl = describe(x), describe(gemm_out), describe(block_tables), describe(context_lens)
-    _check(lib.kv_decode_layerstack(L, ctypes.byref(dx), w_arr, ctypes.byref(dg), q_arr, k_arr, v_arr,
-                                    ctypes.byref(dbt), ctypes.byref(dcl), o_arr, float(scale),
-                                    int(num_kv_heads), int(block_size), int(prefetch_distance),
-                                    int(cross_layer_prefetch), ctypes.c_void_p(_stream_handle(stream))))
+    _call(lambda: lib.kv_decode_layerstack(L, ctypes.byref(dx), w_arr, ctypes.byref(dg), q_arr, k_arr, v_arr,
+                                           ctypes.byref(dbt), ctypes.byref(dcl), o_arr, float(scale),
+                                           int(num_kv_heads), int(block_size), int(prefetch_distance),
+                                           int(cross_layer_prefetch), ctypes.c_void_p(_stream_handle(stream))), x.device)
     return outs
 
 

@@ -320,9 +320,14 @@ template <Elem E, int D, int BS, int PD>
 int launch_one(const AttnParams& p, hipStream_t stream) {
     auto kern = attn_twophase_kernel<E, D, BS, PD>;
     const int lds = twophase_worker_lds_bytes(PD, D, p.G);
-    if (lds > 64 * 1024) {                      // beyond the default limit of dynamic LDS: raise it once per kernel
-        static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (raised != hipSuccess) return -1;
+    // beyond the default limit of dynamic LDS the limit is raised, once, to what the widest group of query heads
+    // needs: the size of a launch depends on the call's group size, the limit must cover every later call
+    constexpr int kMaxGroup = 16;
+    const int lds_max = twophase_worker_lds_bytes(PD, D, kMaxGroup);
+    if (p.G > kMaxGroup) return -1;
+    if (lds_max > 64 * 1024) {
+        static LdsLimit limit;
+        if (limit.raise(reinterpret_cast<const void*>(kern), lds_max) != 0) return -1;
     }
     hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), (size_t)lds, stream, p);
     return 0;

@@ -23,16 +23,32 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
-std::mutex g_ws_mutex;
-void* g_ws_ptr = nullptr;
-size_t g_ws_bytes = 0;
-void* g_trace_ptr = nullptr;         // optional per-worker timestamps (under g_ws_mutex)
+// Per-device state, under g_state_mutex.  The registered workspace is handed out in slices, one per stream that
+// has called: calls on one stream run in stream order and may share a slice, calls on different streams may
+// overlap in time and must not.  A slice is carved from the end of what is in use the first time a stream calls
+// (or when it needs more than it has; its old slice is then abandoned until the workspace is registered again),
+// so a call finds its slice with a short search and nothing is ever waited for.  Each slot also owns the side
+// stream and the two events of the layer stack's cross-layer touch, created when first needed.
+struct StreamSlot {
+    hipStream_t stream = nullptr;
+    size_t offset = 0, bytes = 0;
+    hipStream_t side = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+struct DeviceState {
+    void* ws_ptr = nullptr;
+    size_t ws_bytes = 0, ws_used = 0;
+    std::vector<StreamSlot> slots;
+};
+std::mutex g_state_mutex;
+DeviceState g_dev[kvp::kMaxDevices];
+void* g_trace_ptr = nullptr;         // optional per-worker timestamps (under g_state_mutex)
 size_t g_trace_bytes = 0;
 std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
 std::atomic<int> g_variant{KV_VARIANT_ONE_PASS};   // kernel form of kv_decode_attn on 16-bit caches
 std::atomic<int> g_l2_touch{0};      // tiles per group of the L2 touch wave (0 = none); calls with prefetch_distance 0 only
 std::atomic<int> g_xcd_skew{20};     // per 1024: even workers get 1024 + 20 parts of the tile space, odd ones 1024 - 20
-constexpr int kMaxDevices = 64;
+using kvp::kMaxDevices;
 std::atomic<int> g_num_cus[kMaxDevices];   // compute units per device ordinal, read once each (0 = not read yet)
 
 constexpr int kLdsBytesPerCU = 160 * 1024;
@@ -95,6 +111,7 @@ struct Resolved {
     kvp::AttnParams p;
     int elem, d, bs;
     bool kv8, two_phase;
+    size_t partial_bytes;       // split-KV scratch the launch writes and the merge kernel reads
 };
 
 int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
@@ -186,15 +203,60 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
     p.xcd_skew = g_xcd_skew.load();
     p.l2_touch = (!kv8 && !r->two_phase && prefetch_distance == 0) ? g_l2_touch.load() : 0;
-    const size_t need = kvp::kGemmTicketBytes + kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
-    if (!g_ws_ptr || g_ws_bytes < need)
-        return fail(KV_ERR_WORKSPACE, "kv_decode_attn: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
-    p.partials = (float*)((unsigned char*)g_ws_ptr + kvp::kGemmTicketBytes);
-    p.worker_trace = g_trace_bytes >= (size_t)p.num_workers * 32 ? (unsigned long long*)g_trace_ptr : nullptr;
+    r->partial_bytes = kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
+    p.partials = nullptr;           // bound by bind_registered
+    p.worker_trace = nullptr;
     return KV_OK;
 }
 
+int current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    return dev;
+}
+
+// The slice of the current device's registered workspace that calls on `stream` use, at least `need` bytes.
+// Caller holds g_state_mutex.
+int acquire_slice(DeviceState& ds, hipStream_t stream, size_t need, const char* who, StreamSlot** out) {
+    if (!ds.ws_ptr) return fail(KV_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, none registered on this device", who, need);
+    StreamSlot* slot = nullptr;
+    for (StreamSlot& sl : ds.slots)
+        if (sl.stream == stream) { slot = &sl; break; }
+    if (slot && slot->bytes >= need) { *out = slot; return KV_OK; }
+    if (slot && slot->bytes > 0 && slot->offset + slot->bytes == ds.ws_used && slot->offset + need <= ds.ws_bytes) {
+        slot->bytes = need;                 // the slice at the end of what is in use grows in place
+        ds.ws_used = slot->offset + need;
+        *out = slot;
+        return KV_OK;
+    }
+    const size_t offset = (ds.ws_used + 255) & ~(size_t)255;
+    if (offset + need > ds.ws_bytes)
+        return fail(KV_ERR_WORKSPACE, "%s: workspace of %zu bytes needed for this stream, %zu registered of which %zu are in use "
+                    "by %zu stream(s); register a larger one (registering again also releases every stream's slice)",
+                    who, need, ds.ws_bytes, ds.ws_used, ds.slots.size());
+    if (!slot) {
+        ds.slots.emplace_back();
+        slot = &ds.slots.back();
+        slot->stream = stream;
+    }
+    slot->offset = offset;
+    slot->bytes = need;
+    ds.ws_used = offset + need;
+    *out = slot;
+    return KV_OK;
+}
+
+// Points a resolved call at its stream's slice of the registered workspace: [ticket words][attention partials].
+int bind_registered(Resolved& r, hipStream_t stream, const char* who) {
+    const int dev = current_device();
+    if (dev < 0) return fail(KV_ERR_HIP, "%s: cannot read the current device", who);
+    std::lock_guard<std::mutex> lock(g_state_mutex);
+    StreamSlot* slot = nullptr;
+    if (int rc = acquire_slice(g_dev[dev], stream, kvp::kGemmTicketBytes + r.partial_bytes, who, &slot)) return rc;
+    r.p.partials = (float*)((unsigned char*)g_dev[dev].ws_ptr + slot->offset + kvp::kGemmTicketBytes);
+    r.p.worker_trace = g_trace_bytes >= (size_t)r.p.num_workers * 32 ? (unsigned long long*)g_trace_ptr : nullptr;
+    return KV_OK;
+}
 
 // Optional per-call timing: two events per call, one on each side of the main attention kernel, recorded on
 // the call's stream (the merge kernel that follows is outside the bracket).
@@ -204,11 +266,7 @@ int g_prof_capacity = 0, g_prof_calls = 0, g_prof_every = 1, g_prof_seen = 0;
 
 hipEvent_t prof_event(int call, int which) { return g_prof_events[(size_t)call * 2 + which]; }
 
-// Side stream of the layer stack's cross-layer touch (default priority, created on first use).
-std::mutex g_side_mutex;
-hipStream_t g_side_stream = nullptr;
-hipEvent_t g_fork_event = nullptr, g_join_event = nullptr;
-constexpr int kTouchTiles = 4;          // leading 16-token tiles of every worker's range that get touched
+constexpr int kTouchTiles = 4;          // leading 16-token tiles of every worker's range that the cross-layer touch reads
 
 int check_launch(const char* what) {
     hipError_t e = hipGetLastError();
@@ -246,6 +304,7 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
     if (int rc = resolve(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
                          block_size, prefetch_distance, &r))
         return rc;
+    if (int rc = bind_registered(r, (hipStream_t)stream, "kv_decode_attn")) return rc;
     return run_attn(r, (hipStream_t)stream);
 }
 
@@ -256,6 +315,7 @@ int kv_decode_fetch_probe(const kv_tensor* q, const kv_tensor* k_cache, const kv
     if (int rc = resolve(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
                          block_size, prefetch_distance, &r))
         return rc;
+    if (int rc = bind_registered(r, (hipStream_t)stream, "kv_decode_fetch_probe")) return rc;
     std::unique_lock<std::mutex> prof_lock(g_prof_mutex);
     int slot = -1;
     if (g_prof_capacity > 0 && g_prof_calls < g_prof_capacity && (g_prof_seen++ % g_prof_every) == 0) slot = g_prof_calls++;
@@ -277,6 +337,7 @@ int kv_decode_attn_kv8(const kv_tensor* q, const kv_tensor* k_cache, const kv_te
     if (int rc = resolve(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
                          block_size, prefetch_distance, &r, true, k_scale, v_scale))
         return rc;
+    if (int rc = bind_registered(r, (hipStream_t)stream, "kv_decode_attn_kv8")) return rc;
     return run_attn(r, (hipStream_t)stream);
 }
 
@@ -326,52 +387,71 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
                     (long long)M, (long long)K, (long long)K, (long long)N);
     hipStream_t main_stream = (hipStream_t)stream;
 
-    // weights in operand order: the dense layer splits K over two workgroups per column tile, which meet through
-    // ticket words at the head of the workspace and partial tiles behind the attention's region
-    bool any_operand = false;
-    for (int l = 0; l < num_layers; ++l) any_operand = any_operand || weights[l]->ndim == 5;
-    int* gemm_tickets = nullptr;
-    float* gemm_partials = nullptr;
-    if (any_operand) {
-        const size_t attn_region = attn_partial_region((int)Hq, (int)d);
-        const size_t need = kvp::kGemmTicketBytes + attn_region + kvp::layer_gemm_packed_partial_bytes((int)N);
-        std::lock_guard<std::mutex> lock(g_ws_mutex);
-        if (!g_ws_ptr || g_ws_bytes < need)
-            return fail(KV_ERR_WORKSPACE, "kv_decode_layerstack: workspace of %zu bytes needed, %zu registered", need, g_ws_bytes);
-        gemm_tickets = (int*)g_ws_ptr;
-        gemm_partials = (float*)((unsigned char*)g_ws_ptr + kvp::kGemmTicketBytes + attn_region);
-        // the ticket words must be zero when the first dense layer starts (every launch leaves them zero again);
-        // a fill kernel rather than a memset, so that the call can be captured into a graph
-        kvp::launch_zero_words(gemm_tickets, (int)(kvp::kGemmTicketBytes / sizeof(int)), main_stream);
-    }
-
     // queries of layer l: the caller's tensor, or the leading Hq*d columns of the GEMM output viewed [B, Hq, d]
     kv_tensor qview;
     qview.data = gemm_out->data; qview.dtype = KV_BF16; qview.ndim = 3;
     qview.shape[0] = B; qview.shape[1] = Hq; qview.shape[2] = d;
     qview.stride[0] = gemm_out->stride[0]; qview.stride[1] = d; qview.stride[2] = 1;
 
-    const bool touch = cross_layer_prefetch != 0;
-    if (touch) {
-        std::lock_guard<std::mutex> lock(g_side_mutex);
-        if (!g_side_stream) {
-            hipError_t e = hipStreamCreateWithFlags(&g_side_stream, hipStreamNonBlocking);
-            if (e == hipSuccess) e = hipEventCreateWithFlags(&g_fork_event, hipEventDisableTiming);
-            if (e == hipSuccess) e = hipEventCreateWithFlags(&g_join_event, hipEventDisableTiming);
-            if (e != hipSuccess) return fail(KV_ERR_HIP, "kv_decode_layerstack: side stream: %s", hipGetErrorString(e));
-        }
-    }
+    // every layer's attention call is checked before anything is enqueued
+    std::vector<Resolved> layers((size_t)num_layers);
+    size_t attn_bytes = 0;
     for (int l = 0; l < num_layers; ++l) {
-        const kv_tensor* ql = q ? q[l] : &qview;
-        Resolved r;
-        if (int rc = resolve(ql, k_caches[l], v_caches[l], block_tables, context_lens, outs[l], scale, num_kv_heads,
-                             block_size, prefetch_distance, &r))
+        if (int rc = resolve(q ? q[l] : &qview, k_caches[l], v_caches[l], block_tables, context_lens, outs[l], scale,
+                             num_kv_heads, block_size, prefetch_distance, &layers[(size_t)l]))
             return rc;
-        if (touch) {        // fork: touch this layer's leading KV tiles while the dense layer runs
-            (void)hipEventRecord(g_fork_event, main_stream);
-            (void)hipStreamWaitEvent(g_side_stream, g_fork_event, 0);
-            kvp::launch_touch_mfma(r.p, r.d, r.bs, kTouchTiles, (uint32_t*)r.p.partials, g_side_stream);
-            (void)hipEventRecord(g_join_event, g_side_stream);
+        attn_bytes = layers[(size_t)l].partial_bytes > attn_bytes ? layers[(size_t)l].partial_bytes : attn_bytes;
+    }
+
+    // this stream's slice of the workspace: [ticket words][attention partials][partial tiles of the dense layer].
+    // With weights in operand order the dense layer splits K over two workgroups per column tile, which meet
+    // through the ticket words and the partial tiles.
+    bool any_operand = false;
+    for (int l = 0; l < num_layers; ++l) any_operand = any_operand || weights[l]->ndim == 5;
+    const size_t attn_region = (attn_bytes + 255) & ~(size_t)255;
+    const size_t need = kvp::kGemmTicketBytes + attn_region + (any_operand ? kvp::layer_gemm_packed_partial_bytes((int)N) : 0);
+    const bool touch = cross_layer_prefetch != 0;
+    const int dev = current_device();
+    if (dev < 0) return fail(KV_ERR_HIP, "kv_decode_layerstack: cannot read the current device");
+    unsigned char* slice = nullptr;
+    unsigned long long* trace = nullptr;
+    hipStream_t side = nullptr;
+    hipEvent_t fork_event = nullptr, join_event = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_state_mutex);
+        StreamSlot* slot = nullptr;
+        if (int rc = acquire_slice(g_dev[dev], main_stream, need, "kv_decode_layerstack", &slot)) return rc;
+        slice = (unsigned char*)g_dev[dev].ws_ptr + slot->offset;
+        trace = g_trace_bytes >= (size_t)layers[0].p.num_workers * 32 ? (unsigned long long*)g_trace_ptr : nullptr;
+        if (touch && !slot->side) {        // side stream (default priority) and the fork / join events of this stream's calls
+            hipError_t e = hipStreamCreateWithFlags(&slot->side, hipStreamNonBlocking);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&slot->fork, hipEventDisableTiming);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&slot->join, hipEventDisableTiming);
+            if (e != hipSuccess) {
+                if (slot->side) (void)hipStreamDestroy(slot->side);
+                if (slot->fork) (void)hipEventDestroy(slot->fork);
+                slot->side = nullptr; slot->fork = nullptr; slot->join = nullptr;
+                return fail(KV_ERR_HIP, "kv_decode_layerstack: side stream: %s", hipGetErrorString(e));
+            }
+        }
+        side = slot->side; fork_event = slot->fork; join_event = slot->join;
+    }
+    int* gemm_tickets = (int*)slice;
+    float* attn_partials = (float*)(slice + kvp::kGemmTicketBytes);
+    float* gemm_partials = (float*)(slice + kvp::kGemmTicketBytes + attn_region);
+    // the ticket words must be zero when the first dense layer starts (every launch leaves them zero again);
+    // a fill kernel rather than a memset, so that the call can be captured into a graph
+    if (any_operand) kvp::launch_zero_words(gemm_tickets, (int)(kvp::kGemmTicketBytes / sizeof(int)), main_stream);
+
+    for (int l = 0; l < num_layers; ++l) {
+        Resolved& r = layers[(size_t)l];
+        r.p.partials = attn_partials;
+        r.p.worker_trace = trace;
+        if (touch) {        // fork: touch this layer's leading KV tiles while the dense layer in front of its attention runs
+            (void)hipEventRecord(fork_event, main_stream);
+            (void)hipStreamWaitEvent(side, fork_event, 0);
+            kvp::launch_touch_mfma(r.p, r.d, r.bs, kTouchTiles, (uint32_t*)r.p.partials, side);
+            (void)hipEventRecord(join_event, side);
         }
         const kv_tensor* wl = weights[l];
         int grc;
@@ -387,7 +467,7 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
         if (grc == -2) return fail(KV_ERR_HIP, "kv_decode_layerstack: could not raise the dynamic LDS limit of the GEMM kernel");
         if (grc != 0) return fail(KV_ERR_UNSUPPORTED, "kv_decode_layerstack: GEMM shape not covered");
         if (int rc = check_launch("kv_decode_layerstack GEMM kernel")) return rc;
-        if (touch) (void)hipStreamWaitEvent(main_stream, g_join_event, 0);
+        if (touch) (void)hipStreamWaitEvent(main_stream, join_event, 0);
         if (int rc = run_attn(r, main_stream)) return rc;
     }
     return KV_OK;
@@ -407,9 +487,17 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {
     if ((dev_ptr == nullptr) != (bytes == 0))
         return fail(KV_ERR_INVALID, "kv_decode_set_workspace: pointer and size must both be set or both be zero");
     if (((uintptr_t)dev_ptr) % 16) return fail(KV_ERR_INVALID, "kv_decode_set_workspace: pointer must be 16-byte aligned");
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
-    g_ws_ptr = dev_ptr;
-    g_ws_bytes = bytes;
+    const int dev = current_device();
+    if (dev < 0) {
+        if (!dev_ptr) return KV_OK;          // no device: nothing can be registered, so nothing is left to unregister
+        return fail(KV_ERR_HIP, "kv_decode_set_workspace: cannot read the current device");
+    }
+    std::lock_guard<std::mutex> lock(g_state_mutex);
+    DeviceState& ds = g_dev[dev];
+    ds.ws_ptr = dev_ptr;
+    ds.ws_bytes = bytes;
+    ds.ws_used = 0;
+    for (StreamSlot& sl : ds.slots) { sl.offset = 0; sl.bytes = 0; }    // every stream takes a new slice at its next call
     return KV_OK;
 }
 
@@ -417,7 +505,7 @@ int kv_decode_set_worker_trace(void* dev_ptr, size_t bytes) {
     if ((dev_ptr == nullptr) != (bytes == 0))
         return fail(KV_ERR_INVALID, "kv_decode_set_worker_trace: pointer and size must both be set or both be zero");
     if (((uintptr_t)dev_ptr) % 8) return fail(KV_ERR_INVALID, "kv_decode_set_worker_trace: pointer must be 8-byte aligned");
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    std::lock_guard<std::mutex> lock(g_state_mutex);
     g_trace_ptr = dev_ptr;
     g_trace_bytes = bytes;
     return KV_OK;

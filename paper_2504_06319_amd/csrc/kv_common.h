@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace kvp {
 
 constexpr int kWaveSize = 64;
@@ -69,5 +71,21 @@ constexpr size_t kGemmTicketBytes = 4096;      // head of the workspace: one tic
 int mfma_worker_lds_bytes(int prefetch_distance, int d);
 size_t mfma_partial_bytes(int num_workers, int G, int d);
 constexpr int kMaxMfmaWorkers = 4096;
+constexpr int kMaxDevices = 64;                // device ordinals the library keeps state for
+
+// Dynamic-LDS limit of one kernel: raised to the kernel's own maximum, once per device (the attribute belongs to
+// the device's copy of the function).  Threads that race set the same value.
+struct LdsLimit {
+    std::atomic<int> done[kMaxDevices] = {};
+    // 0, or -2 when HIP refuses
+    int raise(const void* kern, int max_bytes) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -2;
+        if (done[dev].load(std::memory_order_acquire)) return 0;
+        if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, max_bytes) != hipSuccess) return -2;
+        done[dev].store(1, std::memory_order_release);
+        return 0;
+    }
+};
 
 }  // namespace kvp

@@ -211,13 +211,8 @@ int launch_layer_gemm(const void* x, const void* w, void* y, int M, int K, int N
     if (M < 1 || M > kGemmM || K < 4 * kGemmBK || K % (4 * kGemmBK) || N < kGemmBN || N % kGemmBN) return -1;
     // byte offsets inside a k-step are kept in 32 bits
     if ((int64_t)kGemmBK * ldw * 2 + 256 > 0x7fffffffLL || (int64_t)kGemmM * ldx * 2 + 64 > 0x7fffffffLL) return -1;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(layer_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kGemmLds) != hipSuccess)
-            return -2;
-        attr_set = true;
-    }
+    static LdsLimit limit;
+    if (limit.raise(reinterpret_cast<const void*>(layer_gemm_kernel), kGemmLds) != 0) return -2;
     // two workgroups (row halves) per column tile, ids paired 8 apart: round the tile count up to a multiple of 8
     const int tiles = N / kGemmBN;
     const int grid = ((tiles + 7) / 8) * 16;

@@ -279,13 +279,9 @@ __global__ __launch_bounds__(256) void layer_gemm_packed_kernel(const uint16_t* 
 template <int STEPS>
 static int launch_packed(const void* x, const void* wp, void* y, int M, int N, int64_t ldx, int64_t ldy, int* tickets,
                          float* partials, hipStream_t stream) {
-    static bool attr_set = false;
     auto kern = layer_gemm_packed_kernel<STEPS>;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kPkLds) != hipSuccess)
-            return -2;
-        attr_set = true;
-    }
+    static LdsLimit limit;
+    if (limit.raise(reinterpret_cast<const void*>(kern), kPkLds) != 0) return -2;
     const int tiles = N / kPkBN;
     const int grid = ((tiles + 7) / 8) * 16;        // two workgroups per column tile, ids paired 8 apart
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kPkLds, stream, reinterpret_cast<const uint16_t*>(x),

@@ -151,7 +151,7 @@ def test_kv8_entry_point_checks_cache_type_scales_and_alignment():
     # valid arguments get past validation: without a GPU the device query fails (3), with one the missing
     # workspace is reported (4); nothing is launched either way
     lib.kv_decode_set_workspace(None, 0)
-    binding._registered = (0, 0)
+    binding._registered.clear()
     assert call(a) in (3, 4)
 
 
@@ -161,7 +161,7 @@ def test_workspace_registration_arguments_are_checked():
     assert lib.kv_decode_set_workspace(ctypes.c_void_p(0x1000), 0) == 1
     assert lib.kv_decode_set_workspace(None, 64) == 1
     assert lib.kv_decode_set_workspace(ctypes.c_void_p(0x1004), 64) == 1
-    binding._registered = (0, 0)
+    binding._registered.clear()
 
 
 def test_worker_trace_registration_arguments_are_checked():

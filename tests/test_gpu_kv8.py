@@ -110,21 +110,17 @@ def test_empty_batch_rows_single_tokens_and_one_long_sequence():
 
 
 @pytest.mark.parametrize("index", [1, 2, 3])
-def test_benchmark_configurations_at_full_size_sampled(index):
+def test_benchmark_configurations_at_full_size_every_row(index):
     """The benchmark configurations with an 8-bit cache at full size, at the distance bench.py times (1) and
-    without look-ahead; sampled (sequence, head) rows on the oracle, the shortest and the longest sequence included."""
+    without look-ahead; every (sequence, head) row on the oracle."""
     cfg = synth.CONFIGS[index]
     c = synth.make_case_kv8(cfg, synth.config_seed(index), DEV)
-    rng = np.random.default_rng(index)
-    lens = c["lens"]
-    seqs = sorted({int(np.argmin(lens)), int(np.argmax(lens))} | set(rng.integers(0, cfg["B"], 4).tolist()))
-    pairs = [(b, int(h)) for b in seqs for h in rng.choice(cfg["Hq"], 3, replace=False)]
-    want = run_oracle(c, pairs)
+    want = run_oracle(c)
+    assert want.shape == (cfg["B"], cfg["Hq"], cfg["d"])
     for pd in (1, 0):
+        print(f"{cfg['name']}, 8-bit cache: prefetch distance {pd}", flush=True)
         got = run_hip(c, pd)
-        assert torch.isfinite(got.float()).all()
-        g = got.to(torch.float64).cpu().numpy()
-        compare(np.stack([g[b, h] for b, h in pairs]), want, f"{cfg['name']}, 8-bit cache, distance {pd}")
+        compare(got, want, f"{cfg['name']}, 8-bit cache, distance {pd}")
 
 
 def test_wrong_cache_type_and_scales_are_rejected():

@@ -151,6 +151,66 @@ def test_layer_stack_configuration_sampled():
         compare(sub, want, f"stack layer {l}")
 
 
+def _subcase(c, seqs):
+    """The blocks of a few sequences gathered into a small cache of their own (test-side data movement: the oracle
+    then needs one small device-to-host copy per layer instead of the layer's whole 2 GB cache)."""
+    bs = c["block_size"]
+    lens = c["lens"][seqs]
+    nb = (np.maximum(lens, 0) + bs - 1) // bs
+    bt = c["block_tables"].cpu().numpy()
+    ids = np.concatenate([bt[b, :n] for b, n in zip(seqs, nb)]).astype(np.int64)
+    table = np.zeros((len(seqs), int(nb.max())), np.int32)
+    pos = 0
+    for i, n in enumerate(nb):
+        table[i, :n] = np.arange(pos, pos + n)
+        pos += n
+    sel = torch.from_numpy(ids).to(c["k_cache"].device)
+    return dict(k=oracle.bits_of(c["k_cache"][sel]), v=oracle.bits_of(c["v_cache"][sel]), bt=table, cl=lens.astype(np.int32))
+
+
+def test_layer_stack_configuration_at_its_full_depth():
+    """Benchmark configuration 4 as bench.py runs it: all 32 layers resident (32 distinct KV caches, 32 weight
+    matrices in operand order), prefetch distance 2, with and without the cross-layer touch.  The oracle computes
+    the whole output tensor of layers 0, 15 and 31 and every head of 4 random sequences on every layer."""
+    cfg = synth.CONFIGS[4]
+    L, B, Hq, d = cfg["layers"], cfg["B"], cfg["Hq"], cfg["d"]
+    seed = synth.config_seed(4)
+    lens = synth.context_lengths(cfg, seed)
+    _, layers, x, ws, y, outs = _stack(L, B, Hq, cfg["Hkv"], d, cfg["bs"], cfg["gemm_k"], cfg["gemm_n"], lens, seed, poison=False)
+    wp = [kv.pack_weights(w, "operand") for w in ws]
+    print("32 layers resident", flush=True)
+    _run(layers, x, wp, y, outs, pd=2, cross=0)
+    plain = [o.clone() for o in outs]
+    for o in outs:
+        o.fill_(float("nan"))
+    y.fill_(float("nan"))
+    _run(layers, x, wp, y, outs, pd=2, cross=1)
+    for l in range(L):
+        assert torch.equal(outs[l].view(torch.int16), plain[l].view(torch.int16)), f"layer {l}: the touch changed a result"
+    print("both passes done", flush=True)
+    xb = oracle.bits_of(x)
+    rng = np.random.default_rng(44)
+    for l, c in enumerate(layers):
+        wb = oracle.bits_of(ws[l])
+        seqs = np.sort(rng.choice(B, 4, replace=False))
+        # queries of the chosen sequences: their rows of x times the leading Hq * d columns of W_l
+        qrows = oracle.layer_gemm_bf16(xb[seqs], np.ascontiguousarray(wb[:, : Hq * d])).reshape(len(seqs), Hq, d)
+        sub = _subcase(c, seqs)
+        want = oracle.paged_attention(qrows, sub["k"], sub["v"], sub["bt"], sub["cl"], c["scale"], "bf16")
+        compare(outs[l][torch.from_numpy(seqs).to(DEV)], want, f"layer {l}, sequences {seqs.tolist()}")
+        if l in (0, 15, 31):
+            ybits, full = oracle.layerstack_layer(xb, wb, oracle.bits_of(c["k_cache"]), oracle.bits_of(c["v_cache"]),
+                                                  c["block_tables"].cpu().numpy(), c["context_lens"].cpu().numpy(),
+                                                  c["scale"], Hq, d)
+            e_max, e_mean = compare(outs[l], full, f"layer {l}, whole tensor")
+            assert np.array_equal(full[seqs], want), "the gathered sub-cache must give the oracle the same rows"
+            print(f"layer {l}: whole tensor max-abs {e_max:.2e} mean-abs {e_mean:.2e}", flush=True)
+            if l == L - 1:
+                assert _ulp_close_bf16(oracle.bits_of(y), ybits)
+        elif l % 8 == 0:
+            print(f"layer {l} checked", flush=True)
+
+
 @pytest.mark.parametrize("cross", [0, 1])
 def test_layer_stack_can_be_captured_into_a_graph_and_replayed(cross):
     """The whole stack (ticket fill, dense layers, attention, merges, optional side-stream touch) is recorded

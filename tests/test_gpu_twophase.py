@@ -107,6 +107,15 @@ def test_one_pass_and_two_phase_agree_to_rounding():
     assert (one - two).abs().max() <= 2e-2
 
 
+def test_group_sizes_in_any_order_at_the_deepest_look_ahead():
+    """The LDS a worker needs grows with the query heads per kv head; the kernel's dynamic-LDS limit is raised once,
+    to what the widest group needs, so a narrower group (15 heads: 67 584 bytes at distance 4) followed by the widest
+    (16 heads: 69 632 bytes) both launch."""
+    for G in (15, 16, 14, 16):
+        c = synth.make_case(_cfg(G, 1, 128, 16, "bf16"), 260 + G, DEV, poison=True, lens=[900, 0, 17, 2500])
+        compare(run_hip(c, 4), run_oracle(c), f"G = {G} at distance 4")
+
+
 def test_large_lds_launch_and_graph_capture():
     """G = 16 at prefetch distance 4 needs 68 KB of LDS per worker (beyond the default limit of dynamic LDS, which
     the launch raises once), and the comparison modes enqueue only kernels, so a stream capture records them:

@@ -305,17 +305,27 @@ def test_working_set_worked_example_of_the_paper():
 
 
 # ----------------------------------------------------------------------------- Algorithm 1
-@pytest.mark.parametrize("s,e,w", [(0, 1, 4), (0, 4, 4), (3, 22, 4), (5, 5, 2), (0, 64, 8), (7, 40, 3)])
+@pytest.mark.parametrize("first,end,warps", [(0, 1, 4), (0, 4, 4), (3, 22, 4), (5, 5, 2), (0, 64, 8), (7, 40, 3)])
 @pytest.mark.parametrize("distance", [0, 1, 2, 3])
-def test_alg1_index_model_invariants(s, e, w, distance):
-    seen = []
-    for r in range(w):
-        lookups, loads, pre = oracle.alg1_trace(s, e, w, r, distance)
-        assert loads == list(range(s + r, e, w))                       # the warp's stride walk
-        assert pre == loads[distance:] if distance else pre == []      # prefetched = visited minus first k
-        assert all(s <= i < e for i in lookups)                        # nothing at or past e is looked up
-        seen += loads
-    assert sorted(seen) == list(range(s, e))                           # warps cover the range exactly once
+def test_alg1_block_sets(first, end, warps, distance):
+    """Algorithm 1 as sets: between them the warps use every block of the range exactly once; what a warp fetches
+    ahead is exactly what it uses `distance` of its own iterations later (so: everything it uses but its first
+    `distance` blocks, each fetched once); nothing at or past the range end is ever named."""
+    everything = []
+    for rank in range(warps):
+        used = oracle.blocks_used(first, end, warps, rank)
+        assert used == sorted(used) and all(b % warps == (first + rank) % warps for b in used)
+        ahead = oracle.fetches_in_flight(first, end, warps, rank, distance)
+        assert list(ahead) == used
+        fetched = [t for t in ahead.values() if t is not None]
+        assert fetched == (used[distance:] if distance else [])
+        for block, target in ahead.items():
+            if target is not None:
+                assert target == block + distance * warps and first <= target < end
+            else:
+                assert distance == 0 or block + distance * warps >= end        # only the guard suppresses a fetch
+        everything += used
+    assert sorted(everything) == list(range(first, end))
 
 
 # ----------------------------------------------------------------------------- layer stack
