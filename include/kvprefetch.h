@@ -233,11 +233,14 @@ int kv_decode_set_xcd_skew(int per_1024);
  * enabled, every `every`-th kv_decode_attn call records one event before and one after its
  * main kernel (an event pair costs a few microseconds of stream time, hence the sampling).
  * kv_profile_read waits for the recorded calls, returns the summed kernel durations in
- * milliseconds and the number of calls, and rearms the same events.  Calls from several
- * threads share one slot counter under a mutex.
+ * milliseconds and the number of calls, and rearms the same events; kv_profile_read_each does
+ * the same and returns every sample's duration (main_ms holds `capacity` floats; more samples
+ * than that is an error and nothing is consumed), for medians.  Calls from several threads
+ * share one slot counter under a mutex.
  */
 int kv_profile_enable(int max_calls, int every);
 int kv_profile_read(double* main_ms_sum, int* calls);
+int kv_profile_read_each(float* main_ms, int capacity, int* calls);
 
 /*
  * Per-worker timeline of the main attention kernel (where inside a launch the time goes: the

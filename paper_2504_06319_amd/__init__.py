@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     kv_worker_of_tile,
     kv_profile_enable,
     kv_profile_read,
+    kv_profile_read_each,
     kv_iter_working_set_bytes,
     kv_version,
     kv_last_error,

@@ -44,7 +44,7 @@ EXPORTS = [
     "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew", "kv_decode_fetch_probe",
     "kv_decode_set_l2_touch", "kv_decode_set_variant", "kv_decode_get_waves_per_cu_for",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
-    "kv_block_bytes", "kv_iter_working_set_bytes", "kv_worker_range", "kv_worker_of_tile", "kv_profile_enable", "kv_profile_read",
+    "kv_block_bytes", "kv_iter_working_set_bytes", "kv_worker_range", "kv_worker_of_tile", "kv_profile_enable", "kv_profile_read", "kv_profile_read_each",
 ]
 
 
@@ -91,6 +91,8 @@ def load_library():
             lib.kv_profile_enable.argtypes = [ctypes.c_int, ctypes.c_int]
             lib.kv_profile_read.restype = ctypes.c_int
             lib.kv_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+            lib.kv_profile_read_each.restype = ctypes.c_int
+            lib.kv_profile_read_each.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
             lib.kv_last_error.restype = ctypes.c_char_p
             lib.kv_version.restype = ctypes.c_int
             lib.kv_worker_range.restype = ctypes.c_int
@@ -312,6 +314,13 @@ def kv_profile_read():
     a, n = ctypes.c_double(), ctypes.c_int()
     _check(load_library().kv_profile_read(ctypes.byref(a), ctypes.byref(n)))
     return a.value, n.value
+
+
+def kv_profile_read_each(capacity: int = 100000):
+    """Main-kernel milliseconds of every sampled call since the last read, as a list."""
+    buf, n = (ctypes.c_float * capacity)(), ctypes.c_int()
+    _check(load_library().kv_profile_read_each(buf, capacity, ctypes.byref(n)))
+    return list(buf[: n.value])
 
 
 def pack_weights(w: torch.Tensor, layout: str = "operand") -> torch.Tensor:

@@ -597,6 +597,22 @@ int kv_profile_read(double* main_ms_sum, int* calls) {
     return KV_OK;
 }
 
+int kv_profile_read_each(float* main_ms, int capacity, int* calls) {
+    if (!main_ms || !calls || capacity < 0) return fail(KV_ERR_INVALID, "kv_profile_read_each: null output or negative capacity");
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (g_prof_calls > capacity)
+        return fail(KV_ERR_INVALID, "kv_profile_read_each: %d samples recorded, room for %d", g_prof_calls, capacity);
+    *calls = g_prof_calls;
+    for (int i = 0; i < g_prof_calls; ++i) {
+        hipError_t e = hipEventSynchronize(prof_event(i, 1));
+        if (e == hipSuccess) e = hipEventElapsedTime(&main_ms[i], prof_event(i, 0), prof_event(i, 1));
+        if (e != hipSuccess) return fail(KV_ERR_HIP, "kv_profile_read_each: %s", hipGetErrorString(e));
+    }
+    g_prof_calls = 0;
+    g_prof_seen = 0;
+    return KV_OK;
+}
+
 const char* kv_last_error(void) { return g_err; }
 
 int kv_version(void) { return 100; }
