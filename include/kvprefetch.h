@@ -172,6 +172,28 @@ size_t kv_layerstack_workspace_bytes(int num_q_heads, int head_dim, int gemm_n);
 int kv_decode_set_workspace(void* dev_ptr, size_t bytes);
 
 /*
+ * kv_decode_attn for callers that cannot allocate and have no workspace to register: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * checks, kernels and results as kv_decode_attn; the split-KV scratch is a fixed array of
+ * KV_NOALLOC_SCRATCH_BYTES inside the library's device image (every device the library runs on
+ * holds it until the process ends) instead of the registered workspace.  The call allocates
+ * nothing and frees nothing, on the host side of HIP or the device; the first call on a device
+ * looks up the array's address there, later calls read it from a table.  A launch whose pieces
+ * (workers x 2 x Hq/Hkv rows of (d + 4) floats) exceed the array returns KV_ERR_WORKSPACE with
+ * the sizes in kv_last_error() and enqueues nothing: every automatic waves-per-compute-unit
+ * choice on 256 compute units fits, 16 waves with 16 query heads per kv head does not.  Every
+ * call on a device uses that device's one array, whatever the stream: calls that overlap in time
+ * on one device race, calls in stream order do not.  Nothing in the array has to start at zero
+ * (the merge kernel reads only the pieces the same call's main kernel wrote), so none of it is
+ * cleared.
+ */
+#define KV_NOALLOC_SCRATCH_BYTES (32u << 20)
+int kv_decode_attn_noalloc(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+                           const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+                           float scale, int num_kv_heads, int block_size, int prefetch_distance,
+                           void* stream);
+
+/*
  * Persistent waves (workers) per compute unit, 1 .. 16; 0 restores the automatic choice, which
  * aims at 32-48 KB of KV in flight per compute unit: 6 waves at prefetch distance 0 or 1 and 2
  * waves at distance 2 or more for head_dim 128, 8 and 4 waves for head_dim 64.

@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     KV_MAX_PREFETCH_DISTANCE,
     kv_decode_attn,
     kv_decode_attn_kv8,
+    kv_decode_attn_noalloc,
+    KV_NOALLOC_SCRATCH_BYTES,
     kv_decode_get_waves_per_cu_kv8,
     kv_decode_layerstack,
     kv_decode_workspace_bytes,

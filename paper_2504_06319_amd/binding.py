@@ -21,6 +21,7 @@ KV_FP8_E4M3 = 4
 _DTYPE_CODES = {torch.float16: KV_F16, torch.bfloat16: KV_BF16, torch.int32: KV_I32, torch.float32: KV_F32,
                 torch.float8_e4m3fn: KV_FP8_E4M3}
 KV_MAX_PREFETCH_DISTANCE = 4
+KV_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
 class KVError(RuntimeError):
@@ -40,7 +41,7 @@ class KVTensor(ctypes.Structure):
 
 
 EXPORTS = [
-    "kv_decode_attn", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
+    "kv_decode_attn", "kv_decode_attn_noalloc", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
     "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew", "kv_decode_fetch_probe",
     "kv_decode_set_l2_touch", "kv_decode_set_variant", "kv_decode_get_waves_per_cu_for",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
@@ -66,6 +67,8 @@ def load_library():
             lib.kv_decode_attn.restype = ctypes.c_int
             lib.kv_decode_attn.argtypes = [T, T, T, T, T, T, ctypes.c_float, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int, ctypes.c_void_p]
+            lib.kv_decode_attn_noalloc.restype = ctypes.c_int
+            lib.kv_decode_attn_noalloc.argtypes = lib.kv_decode_attn.argtypes
             lib.kv_decode_fetch_probe.restype = ctypes.c_int
             lib.kv_decode_fetch_probe.argtypes = lib.kv_decode_attn.argtypes
             lib.kv_decode_attn_kv8.restype = ctypes.c_int
@@ -217,6 +220,17 @@ def kv_decode_attn(q, k_cache, v_cache, block_tables, context_lens, out, scale, 
     descs = [describe(t) for t in (q, k_cache, v_cache, block_tables, context_lens, out)]
     _call(lambda: lib.kv_decode_attn(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
                                      int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))), q.device)
+    return out
+
+
+def kv_decode_attn_noalloc(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
+                           block_size, prefetch_distance=1, stream=None):
+    """kv_decode_attn on the library's static scratch array: no workspace is created or registered here, and
+    nothing on this path allocates device memory."""
+    lib = load_library()
+    descs = [describe(t) for t in (q, k_cache, v_cache, block_tables, context_lens, out)]
+    _check(lib.kv_decode_attn_noalloc(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
+                                      int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))))
     return out
 
 

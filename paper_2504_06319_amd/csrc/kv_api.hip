@@ -11,6 +11,11 @@
 #include <mutex>
 #include <vector>
 
+// Split-KV scratch of kv_decode_attn_noalloc: a fixed array in the library's own device image instead of memory
+// somebody allocated.  Every device the library runs on holds its own copy at its own address for the life of the
+// process; the name below is a host-side handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[KV_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -39,6 +44,7 @@ struct DeviceState {
     void* ws_ptr = nullptr;
     size_t ws_bytes = 0, ws_used = 0;
     std::vector<StreamSlot> slots;
+    void* scratch_ptr = nullptr;        // device address of g_static_scratch on this device, once resolved
 };
 std::mutex g_state_mutex;
 DeviceState g_dev[kvp::kMaxDevices];
@@ -204,7 +210,7 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.xcd_skew = g_xcd_skew.load();
     p.l2_touch = (!kv8 && !r->two_phase && prefetch_distance == 0) ? g_l2_touch.load() : 0;
     r->partial_bytes = kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
-    p.partials = nullptr;           // bound by bind_registered
+    p.partials = nullptr;           // bound by bind_registered / bind_static
     p.worker_trace = nullptr;
     return KV_OK;
 }
@@ -243,6 +249,29 @@ int acquire_slice(DeviceState& ds, hipStream_t stream, size_t need, const char* 
     slot->bytes = need;
     ds.ws_used = offset + need;
     *out = slot;
+    return KV_OK;
+}
+
+// Points a resolved call at the static scratch array of the current device.  The array's address is looked up once
+// per device, at the first such call there; afterwards this is a table read.  No allocation on any path.
+int bind_static(Resolved& r) {
+    const int dev = current_device();
+    if (dev < 0) return fail(KV_ERR_HIP, "kv_decode_attn_noalloc: cannot read the current device");
+    if (r.partial_bytes > (size_t)KV_NOALLOC_SCRATCH_BYTES)
+        return fail(KV_ERR_WORKSPACE, "kv_decode_attn_noalloc: the launch needs %zu bytes of split-KV scratch (%d workers x 2 pieces x %d "
+                    "query heads per kv head), the static array holds %zu; use fewer waves per compute unit or kv_decode_attn",
+                    r.partial_bytes, r.p.num_workers, r.p.G, (size_t)KV_NOALLOC_SCRATCH_BYTES);
+    std::lock_guard<std::mutex> lock(g_state_mutex);
+    DeviceState& ds = g_dev[dev];
+    if (!ds.scratch_ptr) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(KV_ERR_HIP, "kv_decode_attn_noalloc: address of the static scratch array: %s", hipGetErrorString(e));
+        ds.scratch_ptr = ptr;
+    }
+    r.p.partials = (float*)ds.scratch_ptr;
+    r.p.worker_trace = nullptr;
     return KV_OK;
 }
 
@@ -305,6 +334,17 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
                          block_size, prefetch_distance, &r))
         return rc;
     if (int rc = bind_registered(r, (hipStream_t)stream, "kv_decode_attn")) return rc;
+    return run_attn(r, (hipStream_t)stream);
+}
+
+int kv_decode_attn_noalloc(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
+                           const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
+                           float scale, int num_kv_heads, int block_size, int prefetch_distance, void* stream) {
+    Resolved r;
+    if (int rc = resolve(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,
+                         block_size, prefetch_distance, &r))
+        return rc;
+    if (int rc = bind_static(r)) return rc;
     return run_attn(r, (hipStream_t)stream);
 }
 
