@@ -46,11 +46,8 @@ def event_bracket_overhead(torch, pairs=200):
     return _EVENT_OVERHEAD_MS
 
 
-def timed_steps(kv, torch, cases, pd, steps, warmup):
-    """W untimed + K timed steps, alternating between the cache copies.  Returns
-    (ms per step by wall clock, main-kernel ms per launch by HIP events on the launch stream, less what an
-    empty event bracket reads)."""
-    overhead = event_bracket_overhead(torch)
+def attn_step(kv, cases, pd):
+    """step(i): one attention call (main + merge kernel) on cache copy i % len(cases)."""
     def step(i):
         c = cases[i % len(cases)]
         if "k_scale" in c:                       # 8-bit cache
@@ -59,6 +56,40 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
         else:
             kv.kv_decode_attn(c["q"], c["k_cache"], c["v_cache"], c["block_tables"], c["context_lens"], c["out"],
                               c["scale"], c["num_kv_heads"], c["block_size"], pd)
+    return step
+
+
+def median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2] if len(xs) % 2 else 0.5 * (xs[len(xs) // 2 - 1] + xs[len(xs) // 2])
+
+
+def prewarm(kv, torch, step, min_ms=50.0, max_ms=1500.0, block=16):
+    """Untimed runs of the same call until the chip has settled: the GPU's clocks ramp over the first tens of
+    milliseconds of work, and a timed region of a few milliseconds that starts cold reads several per cent
+    slow.  Runs blocks of launches until at least `min_ms` of kernel time have passed and the medians of the
+    last three blocks' event-timed main-kernel durations agree within 1 % (or `max_ms` is reached).  Returns
+    the milliseconds spent and the last block's median."""
+    spent, meds, i = 0.0, [], 0
+    while spent < max_ms:
+        kv.kv_profile_enable(block, 1)
+        for _ in range(block):
+            step(i)
+            i += 1
+        ms = kv.kv_profile_read_each()
+        kv.kv_profile_enable(0, 1)
+        spent += sum(ms)
+        meds.append(median(ms))
+        if spent >= min_ms and len(meds) >= 3 and max(meds[-3:]) <= 1.01 * min(meds[-3:]):
+            break
+    return spent, meds[-1]
+
+
+def timed_steps(kv, torch, step, steps, warmup):
+    """W untimed + K timed steps.  Returns (ms per step by wall clock between two synchronisations, main-kernel
+    ms per launch by HIP events on the launch stream: mean and median of the sampled launches, less what an
+    empty event bracket reads)."""
+    overhead = event_bracket_overhead(torch)
     for i in range(warmup):
         step(i)
     every = 4                                  # every 4th launch of the timed region carries an event pair
@@ -69,41 +100,130 @@ def timed_steps(kv, torch, cases, pd, steps, warmup):
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    main_ms, n = kv.kv_profile_read()
+    each = kv.kv_profile_read_each()
     kv.kv_profile_enable(0, 1)
-    assert n == (steps + every - 1) // every
-    return (t1 - t0) * 1e3 / steps, main_ms / n - overhead
+    assert len(each) == (steps + every - 1) // every
+    return (t1 - t0) * 1e3 / steps, sum(each) / len(each) - overhead, median(each) - overhead
 
 
-def layer_stack(kv, torch, synth, dev, steps, warmup, pd, cross, layers=None):
+def interleaved(kv, torch, legs, rounds=8, block=10, lead_in=4, kernel_events=True):
+    """Several settings of the same workload measured on an equal footing: `rounds` times round-robin over the
+    legs, each turn = the leg's set-up (occupancy, variant), `lead_in` untimed calls and a block of `block` calls.
+    Two passes over that plan, each enqueued in one go with no host synchronisation inside (an idle gap lets the
+    chip's clocks fall, and the launches after it read slow): in the first every block is bracketed by one pair of
+    stream events (time per step with launch gaps and merge kernel, nothing else on the stream); in the second
+    the library brackets every call's main kernel with its own events.  Whatever drifts during the run (clocks,
+    temperature, the box) hits every leg alike, and the order of the legs cannot favour one.
+    legs: list of (name, setup, step).  Returns {name: {"ms_per_step": median over the blocks, "kernel_ms": median
+    over the sampled launches of the blocks; both less what an empty event bracket reads}}."""
+    overhead = event_bracket_overhead(torch)
+    n = 0
+    brackets = {name: [] for name, _, _ in legs}
+    for _ in range(rounds):
+        for name, setup, step in legs:
+            setup()
+            for _ in range(lead_in):
+                step(n)
+                n += 1
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(block):
+                step(n)
+                n += 1
+            b.record()
+            brackets[name].append((a, b))
+    torch.cuda.synchronize()
+    out = {name: {"ms_per_step": median([(a.elapsed_time(b) - overhead) / block for a, b in brackets[name]])}
+           for name, _, _ in legs}
+    if kernel_events:
+        kv.kv_profile_enable(rounds * len(legs) * (lead_in + block), 1)
+        for _ in range(rounds):
+            for name, setup, step in legs:
+                setup()
+                for _ in range(lead_in + block):
+                    step(n)
+                    n += 1
+        each = kv.kv_profile_read_each()
+        kv.kv_profile_enable(0, 1)
+        turn = lead_in + block
+        assert len(each) == rounds * len(legs) * turn
+        for k, (name, _, _) in enumerate(legs):
+            samples = []
+            for r in range(rounds):
+                start = (r * len(legs) + k) * turn
+                samples += each[start + lead_in:start + turn]
+            out[name]["kernel_ms"] = median(samples) - overhead
+    return out
+
+
+def graph_replay(torch, enqueue, calls_per_graph, replays, warm_replays=3):
+    """The same calls recorded once by a stream capture and replayed: what a serving loop that cannot afford
+    launch gaps would do.  `enqueue()` records `calls_per_graph` steps.  Returns ms per step by wall clock."""
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    for _ in range(warm_replays):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / (replays * calls_per_graph)
+
+
+def kernel_sources_digest():
+    """SHA-256 over the sources of the main attention kernel: a counter summary under profiles/ names the digest it
+    was taken at, and is quoted only while the sources still have it."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("decode_attn_mfma.hip", "attn_device.h", "kv_common.h"):
+        with open(os.path.join(ROOT, "paper_2504_06319_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def build_layer_stack(kv, torch, synth, dev, layers=None):
     """Benchmark configuration 4: `layers` x (dense layer [128 x 4096].[4096 x 14336] + paged decode attention on
-    that layer's own KV cache).  Returns ms per stack pass and the bytes one pass must move."""
+    that layer's own KV cache), every layer resident.  Returns (run(pd, cross, stream=None) enqueueing one pass,
+    KV bytes and weight bytes one pass must move, the configuration, the layer count)."""
     cfg = synth.CONFIGS[4]
     L = layers or cfg["layers"]
     seed = synth.config_seed(4)
     lens = synth.context_lengths(cfg, seed)
     cases = [synth.make_case(cfg, seed, dev, lens=lens, data_seed=seed + 1000 * l) for l in range(L)]
     x = synth.randn16((cfg["B"], cfg["gemm_k"]), "bf16", seed + 11, dev)
-    # weights ~ N(0, 0.02), handed over in the library's tile-packed layout (set-up time, not timed)
+    # weights ~ N(0, 0.02), handed over in matrix-core operand order (set-up time, not timed)
     ws = [kv.pack_weights(synth.randn16((cfg["gemm_k"], cfg["gemm_n"]), "bf16", seed + 13 + l, dev) * 0.02) for l in range(L)]
     y = torch.empty((cfg["B"], cfg["gemm_n"]), dtype=torch.bfloat16, device=dev)
     outs = [torch.empty_like(c["q"]) for c in cases]
     c0 = cases[0]
     ks, vs = [c["k_cache"] for c in cases], [c["v_cache"] for c in cases]
 
-    def step():
+    def run(pd, cross):
         kv.kv_decode_layerstack(x, ws, y, None, ks, vs, c0["block_tables"], c0["context_lens"], outs, c0["scale"],
                                 c0["num_kv_heads"], c0["block_size"], pd, cross)
+    kvb = synth.kv_bytes(lens, cfg["Hkv"], cfg["d"]) * L
+    wb = cfg["gemm_k"] * cfg["gemm_n"] * 2 * L
+    return run, kvb, wb, cfg, L
+
+
+def layer_stack(kv, torch, synth, dev, steps, warmup, pd, cross, layers=None):
+    """ms per stack pass by wall clock (W untimed + K timed passes) and the bytes one pass must move."""
+    run, kvb, wb, cfg, L = build_layer_stack(kv, torch, synth, dev, layers)
     for _ in range(warmup):
-        step()
+        run(pd, cross)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        step()
+        run(pd, cross)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    kvb = synth.kv_bytes(lens, cfg["Hkv"], cfg["d"]) * L
-    wb = cfg["gemm_k"] * cfg["gemm_n"] * 2 * L
     return ms, kvb, wb, cfg, L
 
 
@@ -312,11 +432,7 @@ def main():
             out.append(c)
         return cfg, out
 
-    def measure(index, pd, steps, warmup, kv8=False):
-        cfg, cases = make_cases(index, kv8=kv8)
-        kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"], 1 if kv8 else 2)
-        ms, main_ms = timed_steps(kv, torch, cases, pd, steps, warmup)
-        return cfg, cases, kvb, ms, main_ms
+    nowaves = lambda: kv.kv_decode_set_waves_per_cu(args.waves_per_cu)
 
     if args.traffic_calibration:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)      # 1 GiB read + 1 GiB written per copy
@@ -327,7 +443,7 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
-    pd_on = args.prefetch_distance if args.prefetch_distance is not None else (1 if args.kv8 else 2)
+    pd_on = args.prefetch_distance if args.prefetch_distance is not None else (0 if args.kv8 else 2)
     if args.heatmap:
         print(json.dumps({"heatmap": heatmap(kv, torch, synth, dev, pd_on), "prefetch_distance": pd_on,
                           "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, 128)}), flush=True)
@@ -351,14 +467,25 @@ def main():
                           "cross_layer_touch": args.cross_layer_touch}), flush=True)
         return
     log(f"[bench] workload {args.workload} prefetch_distance {pd_on}")
-    cfg, cases, kvb, ms, main_ms = measure(args.workload, pd_on, args.steps, args.warmup, kv8=args.kv8)
+    cfg, cases = make_cases(args.workload, kv8=args.kv8)
+    kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"], 1 if args.kv8 else 2)
+    step_on = attn_step(kv, cases, pd_on)
+    warm_ms, warm_kernel_ms = prewarm(kv, torch, step_on)
+    log(f"[bench] pre-warm: {warm_ms:.0f} ms of kernel time until the duration settled at {warm_kernel_ms:.4f} ms")
+    ms, main_ms, main_ms_median = timed_steps(kv, torch, step_on, args.steps, args.warmup)
     value = kvb / (ms * 1e-3) / 1e9
     achieved = kvb / (main_ms * 1e-3) / 1e9
-    traffic = None
+    traffic, traffic_note = None, None
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg['name']}.json")
     if os.path.exists(tpath) and not args.kv8:
         with open(tpath) as f:
-            traffic = json.load(f).get("traffic_bytes_per_launch")
+            t = json.load(f)
+        if t.get("kernel_sources_digest") == kernel_sources_digest():
+            traffic = t.get("traffic_bytes_per_launch")
+            traffic_note = f"rocprofv3 FETCH_SIZE + WRITE_SIZE per launch from {os.path.relpath(tpath, ROOT)}, taken at these kernel sources"
+        else:
+            traffic_note = (f"{os.path.relpath(tpath, ROOT)} was taken at kernel sources {t.get('kernel_sources_digest')}, "
+                            f"these are {kernel_sources_digest()}: not quoted")
     result = {
         "metric": "decode-attn effective KV GB/s (% of HBM peak), prefetch on vs off; tokens/s",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -370,18 +497,20 @@ def main():
                    "kv_bytes_per_step": kvb, "prefetch_distance": pd_on,
                    "waves_per_cu": (kv.kv_decode_get_waves_per_cu_kv8(pd_on, cfg["d"]) if args.kv8 else
                                     kv.kv_decode_get_waves_per_cu_for(pd_on, cfg["d"], cfg["Hq"] // cfg["Hkv"])),
+                   "prewarm_ms": warm_ms,
                    **({"l2_touch_tiles": args.l2_touch} if args.l2_touch and pd_on == 0 and not args.kv8 else {}),
                    **({"variant": "two-phase"} if args.two_phase and not args.kv8 else {})},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "tokens_per_s": cfg["B"] / (ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note,
                      "kernel": "attn_mfma_kernel (main attention kernel)", "kernel_ms": main_ms,
+                     "kernel_ms_median": main_ms_median,
                      "kernel_ms_event_bracket": main_ms + event_bracket_overhead(torch),
                      "event_bracket_overhead_ms": event_bracket_overhead(torch),
                      "algorithmic_bytes_per_launch": kvb},
     }
-    log(f"[bench] on: {ms:.4f} ms/step, {value:.0f} GB/s; main kernel {main_ms:.4f} ms")
+    log(f"[bench] on: {ms:.4f} ms/step, {value:.0f} GB/s; main kernel {main_ms:.4f} ms (median {main_ms_median:.4f})")
 
     if args.kv8:
         result["config"]["waves_per_cu"] = kv.kv_decode_get_waves_per_cu_kv8(pd_on, cfg["d"])
@@ -389,65 +518,113 @@ def main():
         print(json.dumps(result), flush=True)
         return
     if not args.no_extra:
-        _, _, _, ms0, main0 = measure(args.workload, 0, args.steps, args.warmup)
+        rounds = max(4, min(10, args.steps // 2))
+        # the same K steps recorded into one graph by a stream capture and replayed (a replay costs tens of
+        # microseconds of launch by itself, so a graph of a single step would read slower than eager launches)
+        result["graph_replay"] = {"steps_per_graph": args.steps,
+                                  "ms_per_step": graph_replay(torch, lambda: [step_on(i) for i in range(args.steps)], args.steps, 5)}
+        result["graph_replay"]["value"] = kvb / (result["graph_replay"]["ms_per_step"] * 1e-3) / 1e9
+        log(f"[bench] graph replay: {result['graph_replay']['ms_per_step']:.4f} ms/step")
+        # Prefetch on vs off on an equal footing: the legs are interleaved (round-robin blocks) and medians are
+        # reported, so neither the order of the legs nor a drift of the chip can favour one.  "auto": each leg at
+        # the occupancy the library picks for it (few waves with look-ahead, many without).  Then both legs pinned
+        # to the same occupancy: with two waves per compute unit occupancy cannot hide the HBM latency (the regime
+        # of the paper's baseline kernel, Table 1) and the look-ahead does; with four or six it can.
+        step_off = attn_step(kv, cases, 0)
+        wave_setter = lambda w: (lambda: kv.kv_decode_set_waves_per_cu(w))
+        legs = [("auto_on", nowaves, step_on), ("auto_off", nowaves, step_off)]
+        for wpc in (2, 4, 6):
+            legs += [(f"w{wpc}_on", wave_setter(wpc), step_on), (f"w{wpc}_off", wave_setter(wpc), step_off)]
+        r = interleaved(kv, torch, legs, rounds=rounds)
+        nowaves()
         result["prefetch_off"] = {"prefetch_distance": 0, "waves_per_cu": kv.kv_decode_get_waves_per_cu(0, cfg["d"]),
-                                  "ms_per_step": ms0, "value": kvb / (ms0 * 1e-3) / 1e9,
-                                  "kernel_ms": main0, "speedup_on_vs_off": ms0 / ms}
-        log(f"[bench] off: {ms0:.4f} ms/step")
-        # The two legs above each run at the occupancy the library picks for them (few waves with look-ahead,
-        # many without).  The same comparison at EQUAL occupancy: with two waves per compute unit occupancy
-        # cannot hide the HBM latency (the regime of the paper's baseline kernel, Table 1) and the look-ahead
-        # does; with four or six it can, and the look-ahead adds nothing.
+                                  "ms_per_step": r["auto_off"]["ms_per_step"], "kernel_ms": r["auto_off"]["kernel_ms"],
+                                  "value": kvb / (r["auto_off"]["ms_per_step"] * 1e-3) / 1e9,
+                                  "interleaved_with": {"prefetch_distance": pd_on, "ms_per_step": r["auto_on"]["ms_per_step"],
+                                                       "kernel_ms": r["auto_on"]["kernel_ms"]},
+                                  "speedup_on_vs_off": r["auto_off"]["ms_per_step"] / r["auto_on"]["ms_per_step"],
+                                  "kernel_speedup_on_vs_off": r["auto_off"]["kernel_ms"] / r["auto_on"]["kernel_ms"],
+                                  "method": f"{rounds} interleaved rounds of 10-step blocks, medians"}
+        log(f"[bench] interleaved auto: on {r['auto_on']['ms_per_step']:.4f} off {r['auto_off']['ms_per_step']:.4f} ms/step")
         low = {}
         for wpc in (2, 4, 6):
-            kv.kv_decode_set_waves_per_cu(wpc)
-            _, _, _, l_on, lk_on = measure(args.workload, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
-            _, _, _, l_off, lk_off = measure(args.workload, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
-            low[f"waves_per_cu_{wpc}"] = {"on_ms_per_step": l_on, "off_ms_per_step": l_off, "on_kernel_ms": lk_on,
-                                         "off_kernel_ms": lk_off, "kernel_speedup_on_vs_off": lk_off / lk_on}
-            log(f"[bench] waves/CU {wpc}: on {lk_on:.4f} ms, off {lk_off:.4f} ms kernel")
-        kv.kv_decode_set_waves_per_cu(args.waves_per_cu)
+            on, off = r[f"w{wpc}_on"], r[f"w{wpc}_off"]
+            low[f"waves_per_cu_{wpc}"] = {"on_ms_per_step": on["ms_per_step"], "off_ms_per_step": off["ms_per_step"],
+                                         "on_kernel_ms": on["kernel_ms"], "off_kernel_ms": off["kernel_ms"],
+                                         "kernel_speedup_on_vs_off": off["kernel_ms"] / on["kernel_ms"]}
+            log(f"[bench] waves/CU {wpc}: on {on['kernel_ms']:.4f} ms, off {off['kernel_ms']:.4f} ms kernel")
         result["prefetch_on_vs_off_equal_occupancy"] = low
         others = {}
         for idx in (1, 2, 3):
             if idx == args.workload:
                 continue
             torch.cuda.empty_cache()
-            ocfg, _, okvb, oms, omain = measure(idx, pd_on, max(10, args.steps // 2), max(5, args.warmup // 2))
-            _, _, _, oms0, _ = measure(idx, 0, max(10, args.steps // 2), max(5, args.warmup // 2))
+            ocfg, ocases = make_cases(idx)
+            okvb = synth.kv_bytes(ocases[0]["lens"], ocfg["Hkv"], ocfg["d"])
+            o_on, o_off = attn_step(kv, ocases, pd_on), attn_step(kv, ocases, 0)
+            prewarm(kv, torch, o_on, min_ms=20.0)
+            r = interleaved(kv, torch, [("on", nowaves, o_on), ("off", nowaves, o_off)], rounds=rounds)
+            oms = r["on"]["ms_per_step"]
             others[ocfg["name"]] = {"value": okvb / (oms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_step": oms,
                                     "pct_hbm_peak": 100.0 * okvb / (oms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                    "kernel_ms": omain, "prefetch_off_ms_per_step": oms0,
+                                    "kernel_ms": r["on"]["kernel_ms"], "prefetch_off_ms_per_step": r["off"]["ms_per_step"],
+                                    "prefetch_off_kernel_ms": r["off"]["kernel_ms"],
+                                    "speedup_on_vs_off": r["off"]["ms_per_step"] / oms,
                                     "tokens_per_s": ocfg["B"] / (oms * 1e-3)}
-            log(f"[bench] {ocfg['name']}: on {oms:.4f} ms, off {oms0:.4f} ms")
+            log(f"[bench] {ocfg['name']}: on {oms:.4f} ms, off {r['off']['ms_per_step']:.4f} ms")
+            del ocases, o_on, o_off
         result["other_workloads"] = others
-        # the same workloads on an 8-bit (FP8 E4M3) KV cache: half the bytes per token; GB/s counts the 8-bit bytes
+        # the same workloads on an 8-bit (FP8 E4M3) KV cache: half the bytes per token; GB/s counts the 8-bit bytes.
+        # This kernel needs six waves per compute unit for its arithmetic (the widening), and six waves' own requests
+        # already fill the memory system: look-ahead does not pay here, so the headline leg is distance 0.
         kv8 = {}
         for idx in (1, 2, 3):
             torch.cuda.empty_cache()
-            kcfg, _, kkvb, kms, kmain = measure(idx, 1, max(10, args.steps // 2), max(5, args.warmup // 2), kv8=True)
-            _, _, _, kms0, kmain0 = measure(idx, 0, max(10, args.steps // 2), max(5, args.warmup // 2), kv8=True)
-            kv8[kcfg["name"]] = {"prefetch_distance": 1, "waves_per_cu": kv.kv_decode_get_waves_per_cu_kv8(1, kcfg["d"]),
+            kcfg, kcases = make_cases(idx, kv8=True)
+            kkvb = synth.kv_bytes(kcases[0]["lens"], kcfg["Hkv"], kcfg["d"], 1)
+            k0, k1 = attn_step(kv, kcases, 0), attn_step(kv, kcases, 1)
+            prewarm(kv, torch, k0, min_ms=20.0)
+            r = interleaved(kv, torch, [("pd0", nowaves, k0), ("pd1", nowaves, k1)], rounds=rounds)
+            kms = r["pd0"]["ms_per_step"]
+            kv8[kcfg["name"]] = {"prefetch_distance": 0, "waves_per_cu": kv.kv_decode_get_waves_per_cu_kv8(0, kcfg["d"]),
                                  "kv_bytes_per_step": kkvb, "ms_per_step": kms, "value": kkvb / (kms * 1e-3) / 1e9,
                                  "unit": "GB/s", "pct_hbm_peak": 100.0 * kkvb / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                 "kernel_ms": kmain, "tokens_per_s": kcfg["B"] / (kms * 1e-3),
-                                 "prefetch_off_ms_per_step": kms0, "prefetch_off_kernel_ms": kmain0}
-            log(f"[bench] {kcfg['name']} 8-bit cache: on {kms:.4f} ms, off {kms0:.4f} ms")
+                                 "kernel_ms": r["pd0"]["kernel_ms"], "tokens_per_s": kcfg["B"] / (kms * 1e-3),
+                                 "prefetch_distance_1_ms_per_step": r["pd1"]["ms_per_step"],
+                                 "prefetch_distance_1_kernel_ms": r["pd1"]["kernel_ms"],
+                                 "speedup_distance_1_vs_0": kms / r["pd1"]["ms_per_step"]}
+            log(f"[bench] {kcfg['name']} 8-bit cache: distance 0 {kms:.4f} ms, distance 1 {r['pd1']['ms_per_step']:.4f} ms")
+            del kcases, k0, k1
         result["kv8_cache"] = kv8
-        # layer stack (configuration 4): tokens/s of 32 x (dense layer + attention), prefetch on / off, cross-layer touch
-        del cases
+        # layer stack (configuration 4): tokens/s of 32 x (dense layer + attention); prefetch on / off and the
+        # cross-layer touch interleaved pass by pass, and the whole pass replayed from a captured graph
+        del cases, step_on, step_off, legs
         torch.cuda.empty_cache()
+        run, lkvb, lwb, lcfg, L = build_layer_stack(kv, torch, synth, dev)
+        passes = max(3, args.steps // 5)
+        for _ in range(3):
+            run(pd_on, 0)
+        torch.cuda.synchronize()
+        r = interleaved(kv, torch, [("on", nowaves, lambda i: run(pd_on, 0)), ("on_cross_layer_touch", nowaves, lambda i: run(pd_on, 1)),
+                                    ("off", nowaves, lambda i: run(0, 0))], rounds=passes, block=1, lead_in=1, kernel_events=False)
         ls = {}
-        for name, pd_, cross in (("on", pd_on, 0), ("on_cross_layer_touch", pd_on, 1), ("off", 0, 0)):
-            lms, lkvb, lwb, lcfg, L = layer_stack(kv, torch, synth, dev, max(3, args.steps // 20), 2, pd_, cross)
-            torch.cuda.empty_cache()
+        for name in ("on", "on_cross_layer_touch", "off"):
+            lms = r[name]["ms_per_step"]
             ls[name] = {"ms_per_pass": lms, "tokens_per_s": lcfg["B"] / (lms * 1e-3), "GB_per_s": (lkvb + lwb) / (lms * 1e-3) / 1e9,
                         "pct_hbm_peak": 100.0 * (lkvb + lwb) / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS}
             log(f"[bench] layer stack {name}: {lms:.3f} ms/pass, {lcfg['B'] / (lms * 1e-3):.0f} tokens/s")
+        gms = graph_replay(torch, lambda: run(pd_on, 0), 1, passes)
+        ls["on_graph_replay"] = {"ms_per_pass": gms, "tokens_per_s": lcfg["B"] / (gms * 1e-3), "GB_per_s": (lkvb + lwb) / (gms * 1e-3) / 1e9,
+                                 "pct_hbm_peak": 100.0 * (lkvb + lwb) / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        log(f"[bench] layer stack graph replay: {gms:.3f} ms/pass")
+        ls["speedup_on_vs_off"] = ls["off"]["ms_per_pass"] / ls["on"]["ms_per_pass"]
         ls["layers"] = L
         ls["kv_bytes_per_pass"] = lkvb
         ls["weight_bytes_per_pass"] = lwb
+        ls["method"] = f"{passes} interleaved rounds of single passes, medians (3 untimed passes first)"
         result["layer_stack"] = ls
+        del run
+        torch.cuda.empty_cache()
         cfg, cases = make_cases(args.workload, copies=1)
 
     if not args.no_cpu_baseline:

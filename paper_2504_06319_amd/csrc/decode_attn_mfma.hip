@@ -355,78 +355,108 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
     }
 }
 
-// Merge of the pieces of every unit that more than one worker touched, and zero rows for empty
-// sequences.  One workgroup per (query head, sequence), one thread per output column.
+// Merge of the pieces of every unit that more than one worker touched, and zero rows for empty sequences.
 //   out[h, c] = sum_i 2^(m_i - m*) acc_i[c] / sum_i 2^(m_i - m*) l_i,   m* = max_i m_i
-// Piece i was written by worker w0 + i; only the first worker can hold the unit as the piece at the END
-// of its range (slot 1), every later worker holds it as the piece at the start (slot 0).
-// The kernel is a chain of dependent memory round trips, so it is written to have two of them: one pass
-// over context_lens, then every load of a batch of pieces (max, sum and accumulator column) in flight at
-// once, each thread keeping its own running (m*, sum, acc) across batches.
-template <Elem E, int D>
-__global__ __launch_bounds__(D) void attn_finalize_kernel(AttnParams p, int bs) {
+// One workgroup per WORKER of the main launch, not per output row: a worker's range ends inside at most one
+// unit, so the units that need a merge are found from the workers' range ends, and a launch has as many
+// workgroups as the main kernel had waves (512 at two waves per compute unit) instead of one per (query head,
+// sequence) that each had to find out whether anything was cut.  Workgroup w merges the unit that holds the last
+// tile of worker w's range, if that unit goes on past the range end and began inside the range (so that w holds
+// its first piece: exactly one workgroup qualifies per cut unit).  Piece i of the unit was written by worker
+// w + i; only the first can hold it as the piece at the END of its range (slot 1), every later worker holds it
+// as the piece at the start (slot 0).  All G query heads of the unit are merged here, IT (head, column) pairs
+// per thread; the kernel is a chain of dependent memory round trips, so it is written to have few of them: the
+// scan of context_lens, then every load of a batch of 32 / IT pieces (max, sum and accumulator column) in flight
+// at once, each thread keeping its running (m*, sum, acc) across batches.
+// Empty sequences: workgroup w writes the zero rows of sequences w, w + gridDim.x, ...
+template <Elem E, int D, int IT>
+__global__ __launch_bounds__(256) void attn_finalize_kernel(AttnParams p, int bs) {
     constexpr int PS = Geo<D>::kPartialStride;
-    const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x, lane = c % kWaveSize;
-    const int G = p.G, Hkv = p.Hkv, kvh = h / G, g = h % G;
+    constexpr int U = 32 / IT;                          // pieces per batch
+    const int w = blockIdx.x, tid = threadIdx.x, lane = tid % kWaveSize;
+    const int G = p.G, Hkv = p.Hkv;
     const int max_len = p.MB * bs;
     const_i32_ptr cl = (const_i32_ptr)p.context_lens;
-    uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)b * p.out_stride_b + (int64_t)h * p.out_stride_h;
 
-    // one pass over the lengths: tiles of the batch, of the sequences before b, and of b itself
-    int total = 0, cum = 0, nt = 0;
-    for (int base = 0; base < p.B; base += kWaveSize) {
-        const int idx = base + lane;
-        const int t = idx < p.B ? tiles_of(clamp_len(cl[idx], max_len), p.tile_shift) : 0;
-        total += wave_sum_i32(t);
-        cum += wave_sum_i32(idx < b ? t : 0);
-        if (b >= base && b < base + kWaveSize) nt = __builtin_amdgcn_readlane(t, b - base);
+    for (int b = w; b < p.B; b += gridDim.x) {          // zero rows of empty contexts
+        if (tiles_of(clamp_len(cl[b], max_len), p.tile_shift) != 0) continue;
+        uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)b * p.out_stride_b;
+        for (int idx = tid; idx < p.Hq * D; idx += 256) orow[(int64_t)(idx / D) * p.out_stride_h + idx % D] = 0;
     }
-    if (nt == 0) {                                  // empty context: zero row
-        orow[c] = 0;
-        return;
-    }
+
+    const int total = scan_total(cl, p.B, max_len, lane, p.tile_shift);
     const int64_t T = (int64_t)total * Hkv;
     const int nw = T < p.num_workers ? (int)T : p.num_workers;
-    const int64_t a = (int64_t)Hkv * cum + (int64_t)kvh * nt, end = a + nt;     // the unit's flat tile range
+    if (w >= nw) return;
     const int skew = effective_skew(T, nw, p.xcd_skew);
-    const int w0 = range_owner(a, T, nw, skew);         // last worker whose range starts at or before a
+    const int64_t r0 = range_start(w, T, nw, skew), r1 = range_start(w + 1, T, nw, skew);
+    if (r1 >= T) return;                                // the last worker's range ends with the last unit
+    int b, cum, n;
+    scan_locate(cl, p.B, max_len, lane, p.tile_shift, Hkv, r1 - 1, b, cum, n);
+    const int nt = tiles_of(n, p.tile_shift);
+    const int kvh = (int)((r1 - 1 - (int64_t)Hkv * cum) / nt);
+    const int64_t a = (int64_t)Hkv * cum + (int64_t)kvh * nt, end = a + nt;      // the unit's flat tile range
+    if (end <= r1 || a < r0) return;                    // not cut at this range's end, or its first piece is an earlier worker's
     const int w1 = range_owner(end - 1, T, nw, skew);   // last worker whose range starts before end
-    if (w0 == w1) return;                           // one worker covered the unit and wrote the rows itself
-    const int np = w1 - w0 + 1;
-    const int slot_first = range_starts_before(w0, a, T, nw, skew) ? 1 : 0;
-    const float* first_row = p.partials + ((int64_t)(w0 * 2 + slot_first) * G + g) * PS;
-    const float* later_rows = p.partials + ((int64_t)(w0 * 2) * G + g) * PS;     // + i * 2 * G * PS for piece i >= 1
+    const int np = w1 - w + 1;
+    const int slot_first = a > r0 ? 1 : 0;
 
-    float num = 0.f, den = 0.f, mrun = kNegBig;
-    auto batch = [&](int base, int cnt, auto tag) {
-        constexpr int U = decltype(tag)::value;
-        float2 ml[U];
-        float v[U];
+    // this thread's (head, column) pairs: idx = tid + 256 k < G * D
+    const float* first_row[IT];
+    const float* later_rows[IT];                        // + i * 2 * G * PS for piece i >= 1
+    int col[IT];
+    bool live[IT];
+#pragma unroll
+    for (int k = 0; k < IT; ++k) {
+        const int idx = tid + 256 * k;
+        live[k] = idx < G * D;
+        const int g = live[k] ? idx / D : 0;
+        col[k] = idx % D;
+        first_row[k] = p.partials + ((int64_t)(w * 2 + slot_first) * G + g) * PS;
+        later_rows[k] = p.partials + ((int64_t)(w * 2) * G + g) * PS;
+    }
+    float num[IT], den[IT], mrun[IT];
+#pragma unroll
+    for (int k = 0; k < IT; ++k) { num[k] = 0.f; den[k] = 0.f; mrun[k] = kNegBig; }
+
+    for (int base = 0; base < np; base += U) {
+        const int cnt = min(U, np - base);
+        float2 ml[IT][U];
+        float v[IT][U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = base + min(u, cnt - 1);   // stay on a real piece; surplus slots are ignored below
-            const float* row = i == 0 ? first_row : later_rows + (int64_t)i * 2 * G * PS;
-            ml[u] = *reinterpret_cast<const float2*>(row + D);
-            v[u] = row[c];
-        }
-        float mb = mrun;
+            const int i = base + min(u, cnt - 1);       // stay on a real piece; surplus slots are ignored below
 #pragma unroll
-        for (int u = 0; u < U; ++u) if (u < cnt) mb = fmaxf(mb, ml[u].x);
-        const float resc = fast_exp2(mrun - mb);
-        num *= resc;
-        den *= resc;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float w = u < cnt ? fast_exp2(ml[u].x - mb) : 0.f;
-            num += w * v[u];
-            den += w * ml[u].y;
+            for (int k = 0; k < IT; ++k) {
+                const float* row = i == 0 ? first_row[k] : later_rows[k] + (int64_t)i * 2 * G * PS;
+                ml[k][u] = *reinterpret_cast<const float2*>(row + D);
+                v[k][u] = row[col[k]];
+            }
         }
-        mrun = mb;
-    };
-    int base = 0;
-    for (; np - base > 8; base += 32) batch(base, min(32, np - base), std::integral_constant<int, 32>{});
-    if (base < np) batch(base, np - base, std::integral_constant<int, 8>{});
-    orow[c] = pack1<E>(num / den * p.out_scale);
+#pragma unroll
+        for (int k = 0; k < IT; ++k) {
+            float mb = mrun[k];
+#pragma unroll
+            for (int u = 0; u < U; ++u) if (u < cnt) mb = fmaxf(mb, ml[k][u].x);
+            const float resc = fast_exp2(mrun[k] - mb);
+            num[k] *= resc;
+            den[k] *= resc;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float wgt = u < cnt ? fast_exp2(ml[k][u].x - mb) : 0.f;
+                num[k] += wgt * v[k][u];
+                den[k] += wgt * ml[k][u].y;
+            }
+            mrun[k] = mb;
+        }
+    }
+    uint16_t* obase = reinterpret_cast<uint16_t*>(p.out) + (int64_t)b * p.out_stride_b;
+#pragma unroll
+    for (int k = 0; k < IT; ++k) {
+        if (!live[k]) continue;
+        const int g = (tid + 256 * k) / D;
+        obase[(int64_t)(kvh * G + g) * p.out_stride_h + col[k]] = pack1<E>(num[k] / den[k] * p.out_scale);
+    }
 }
 
 template <Elem E, int D, int BS, int PD>
@@ -513,15 +543,26 @@ size_t mfma_partial_bytes(int num_workers, int G, int d) {
     return (size_t)num_workers * 2 * G * (d + 4) * sizeof(float);
 }
 
-// Merge kernel; always launched after the main kernel (it also writes the zero rows of empty sequences).
+// Merge kernel; always launched after the main kernel (it also writes the zero rows of empty sequences): one
+// workgroup per worker of the main launch.
+template <Elem E, int D>
+static void launch_finalize_it(const AttnParams& p, int bs, hipStream_t stream) {
+    const dim3 grid(p.num_workers), block(256);
+    const int pairs = p.G * D;                      // (head, column) pairs of a unit, 256 threads
+    if (pairs <= 256) hipLaunchKernelGGL((attn_finalize_kernel<E, D, 1>), grid, block, 0, stream, p, bs);
+    else if (pairs <= 512) hipLaunchKernelGGL((attn_finalize_kernel<E, D, 2>), grid, block, 0, stream, p, bs);
+    else if (pairs <= 1024) hipLaunchKernelGGL((attn_finalize_kernel<E, D, 4>), grid, block, 0, stream, p, bs);
+    else hipLaunchKernelGGL((attn_finalize_kernel<E, D, 8>), grid, block, 0, stream, p, bs);
+}
+
 int launch_finalize_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream) {
-    const dim3 grid(p.Hq, p.B);
+    if (p.num_workers < 1 || p.num_workers > kMaxMfmaWorkers || p.G < 1 || p.G > 16) return -1;
     if (elem == (int)Elem::F16) {
-        if (d == 128) hipLaunchKernelGGL((attn_finalize_kernel<Elem::F16, 128>), grid, dim3(128), 0, stream, p, bs);
-        else hipLaunchKernelGGL((attn_finalize_kernel<Elem::F16, 64>), grid, dim3(64), 0, stream, p, bs);
+        if (d == 128) launch_finalize_it<Elem::F16, 128>(p, bs, stream);
+        else launch_finalize_it<Elem::F16, 64>(p, bs, stream);
     } else {
-        if (d == 128) hipLaunchKernelGGL((attn_finalize_kernel<Elem::BF16, 128>), grid, dim3(128), 0, stream, p, bs);
-        else hipLaunchKernelGGL((attn_finalize_kernel<Elem::BF16, 64>), grid, dim3(64), 0, stream, p, bs);
+        if (d == 128) launch_finalize_it<Elem::BF16, 128>(p, bs, stream);
+        else launch_finalize_it<Elem::BF16, 64>(p, bs, stream);
     }
     return 0;
 }
