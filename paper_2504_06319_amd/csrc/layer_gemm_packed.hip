@@ -241,6 +241,14 @@ __global__ __launch_bounds__(256) void layer_gemm_packed_kernel(const uint16_t* 
             for (int i = 0; i < 4; ++i)
                 __hip_atomic_store(mine + base + ((mb * kPkWOwn + nb) * 4 + i) * 64, acc[mb][nb][i], __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
+    // Publication, ordered by what the instructions guarantee rather than by a release / acquire pair: the partial
+    // values are device-scope stores (written through to the level all XCDs share), s_waitcnt vmcnt(0) returns when
+    // they have been acknowledged there, the barrier collects the whole workgroup, and only then does thread 0 draw the
+    // ticket, a device-scope read-modify-write at that same level.  The workgroup that draws the second ticket reads
+    // the other tile with device-scope loads (which bypass the caches that are not coherent between XCDs) issued after
+    // its ticket has returned.  The same exchange with an acquire-release ticket was measured: the compiler brackets it
+    // with a write-back and an invalidate of the whole L2 (buffer_wbl2 / buffer_inv), 38.2 us per launch against
+    // 32.9 us, for lines that never were in a non-coherent cache.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // this thread's partial values are written
     __builtin_amdgcn_s_barrier();                            // ... and so are the whole workgroup's
     int ticket = 0;
