@@ -284,14 +284,15 @@ def worker_timeline(kv, torch, cases, pd, launches=8):
         kv.kv_decode_set_worker_trace(None)
     t = trace.cpu().numpy()
     t = t[t[:, 3] > 0]                         # workers that had a range
-    xcd, t[:, 3] = t[:, 3] >> 32, t[:, 3] & 0xffffffff
+    first_wait_us = ((t[:, 3] >> 40) & 0xffff) / 100.0
+    xcd, t[:, 3] = (t[:, 3] >> 32) & 0xf, t[:, 3] & 0xffffffff
     t0 = t[:, 0].min()
     us = lambda col: (t[:, col] - t0) / 100.0
     pct = lambda a: {f"p{q}": round(float(np.percentile(a, q)), 2) for q in (0, 10, 50, 90, 100)}
     return {"workers": int(len(t)), "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd, cfg_d),
             "tiles_per_worker": [int(t[:, 3].min()), int(t[:, 3].max())],
             "entry_us": pct(us(0)), "range_located_us": pct(us(1)), "exit_us": pct(us(2)),
-            "busy_us": pct((t[:, 2] - t[:, 1]) / 100.0),
+            "busy_us": pct((t[:, 2] - t[:, 1]) / 100.0), "first_tile_wait_us": pct(first_wait_us),
             "mean_exit_us_by_xcd": {int(x): round(float(us(2)[xcd == x].mean()), 2) for x in np.unique(xcd)}}
 
 
@@ -331,6 +332,66 @@ def heatmap(kv, torch, synth, dev, pd_on, steps=20, warmup=4):
                 torch.cuda.empty_cache()
         log(f"[bench] heat-map {name} done")
     return rows
+
+
+def working_set_sweep(kv, torch, synth, dev, pd, launches=40):
+    """Main-kernel rate against the size of the KV working set, the SAME cache on every launch (no alternation):
+    while the set fits the L2s (8 x 4 MB) or the memory-side cache (256 MB) a launch finds lines of the one before,
+    beyond it every byte comes from HBM.  The steps of the curve are the evidence for where the fetches are
+    served from: no counter of the memory-side cache is exposed on this chip."""
+    rows = []
+    B, Hq, Hkv, d, bs = 16, 32, 8, 128, 16
+    for mb in (8, 16, 32, 64, 96, 128, 192, 256, 320, 384, 512, 768, 1024, 2048):
+        ctx = mb * (1 << 20) // (B * Hkv * d * 2 * 2)
+        cfg = dict(Hq=Hq, Hkv=Hkv, d=d, bs=bs, dtype="bf16")
+        c = synth.make_case(cfg, synth.BASE_SEED + mb, dev, lens=[ctx] * B)
+        c["out"] = torch.empty_like(c["q"])
+        step = attn_step(kv, [c], pd)
+        for i in range(10):
+            step(i)
+        kv.kv_profile_enable(launches, 1)
+        for i in range(launches):
+            step(i)
+        each = kv.kv_profile_read_each()
+        kv.kv_profile_enable(0, 1)
+        us = (median(each) - event_bracket_overhead(torch)) * 1e3
+        kvb = synth.kv_bytes([ctx] * B, Hkv, d)
+        rows.append({"kv_megabytes": mb, "context": ctx, "kernel_us": round(us, 1), "GBps": round(kvb / us / 1e3, 0)})
+        log(f"[bench] working set {mb} MB: {us:.1f} us, {kvb / us / 1e3:.0f} GB/s")
+        del c, step
+        torch.cuda.empty_cache()
+    return rows
+
+
+def touch_latency(kv, torch, synth, dev, pd, reps=12):
+    """What the layer stack's cross-layer touch does for the attention kernel that follows it: a two-layer stack at
+    the benchmark's width, with and without the touch (alternating), the attention workers of the last layer
+    reporting how long their first tile pair took to land after they had located their range."""
+    import numpy as np
+    run, _, _, cfg, _ = build_layer_stack(kv, torch, synth, dev, layers=2)
+    trace = torch.zeros((4096, 4), dtype=torch.int64, device=dev)
+    out = {}
+    samples = {0: [], 1: []}
+    ramp = {0: [], 1: []}
+    for _ in range(3):
+        run(pd, 0)
+    kv.kv_decode_set_worker_trace(trace)
+    try:
+        for r in range(reps):
+            for cross in (0, 1):
+                run(pd, cross)
+                torch.cuda.synchronize()
+                t = trace.cpu().numpy()
+                t = t[(t[:, 3] & 0xffffffff) > 0]
+                samples[cross].append(np.median(((t[:, 3] >> 40) & 0xffff) / 100.0))
+                ramp[cross].append(np.percentile((t[:, 1] - t[:, 0].min()) / 100.0, 50) + samples[cross][-1])
+    finally:
+        kv.kv_decode_set_worker_trace(None)
+    for cross in (0, 1):
+        out["touch" if cross else "no_touch"] = {
+            "first_tile_wait_us_median_over_workers": round(float(np.median(samples[cross])), 2),
+            "launch_to_first_tile_us": round(float(np.median(ramp[cross])), 2), "launches": reps}
+    return out
 
 
 def cpu_baseline(oracle, synth, case, cfg, budget_s=20.0, min_wall_s=1.5):
@@ -376,6 +437,8 @@ def main():
     ap.add_argument("--workload", type=int, default=1, choices=[1, 2, 3])
     ap.add_argument("--prefetch-distance", type=int, default=None)
     ap.add_argument("--waves-per-cu", type=int, default=0, help="persistent waves per compute unit (0 = automatic)")
+    ap.add_argument("--prewarm-ms", type=float, default=50.0,
+                    help="untimed pre-warm before the timed region: at least this many ms of kernel time (0 for profiler runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the prefetch-off leg and the other workloads")
     ap.add_argument("--layer-stack-only", type=int, default=0, metavar="LAYERS",
@@ -396,6 +459,15 @@ def main():
     ap.add_argument("--fetch-ceiling", action="store_true",
                     help="time the attention kernel's fetch stream without its arithmetic beside the kernel itself "
                          "over a grid of occupancies and prefetch distances, print the table and exit")
+    ap.add_argument("--fetch-policy", choices=["nt", "plain"], default="nt",
+                    help="cache-policy comparison: 'plain' drops the non-temporal hint from the KV fetches and the dense "
+                         "layer's weight loads (benchmark shapes only)")
+    ap.add_argument("--working-set-sweep", action="store_true",
+                    help="print the main kernel's rate against the size of a KV working set that is re-read by every "
+                         "launch (where L2 and the memory-side cache stop serving it) and exit")
+    ap.add_argument("--touch-latency", action="store_true",
+                    help="print the attention workers' first-tile latency in a two-layer stack with and without the "
+                         "cross-layer touch and exit")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run plain 1 GiB device copies, so a counter run sees a copy kernel of known traffic")
     args = ap.parse_args()
@@ -421,6 +493,8 @@ def main():
         kv.kv_decode_set_l2_touch(args.l2_touch)
     if args.two_phase:
         kv.kv_decode_set_variant(kv.KV_VARIANT_TWO_PHASE)
+    if args.fetch_policy == "plain":
+        kv.kv_decode_set_fetch_policy(kv.KV_FETCH_PLAIN)
 
     def make_cases(index, copies=2, kv8=False):
         cfg = synth.CONFIGS[index]
@@ -448,6 +522,13 @@ def main():
         print(json.dumps({"heatmap": heatmap(kv, torch, synth, dev, pd_on), "prefetch_distance": pd_on,
                           "waves_per_cu": kv.kv_decode_get_waves_per_cu(pd_on, 128)}), flush=True)
         return
+    if args.working_set_sweep:
+        print(json.dumps({"prefetch_distance": pd_on, "fetch_policy": args.fetch_policy,
+                          "working_set_sweep": working_set_sweep(kv, torch, synth, dev, pd_on)}), flush=True)
+        return
+    if args.touch_latency:
+        print(json.dumps({"prefetch_distance": pd_on, "touch_latency": touch_latency(kv, torch, synth, dev, pd_on)}), flush=True)
+        return
     if args.worker_timeline:
         cfg, cases = make_cases(args.workload)
         print(json.dumps({"workload": cfg["name"], "prefetch_distance": pd_on,
@@ -470,7 +551,7 @@ def main():
     cfg, cases = make_cases(args.workload, kv8=args.kv8)
     kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"], 1 if args.kv8 else 2)
     step_on = attn_step(kv, cases, pd_on)
-    warm_ms, warm_kernel_ms = prewarm(kv, torch, step_on)
+    warm_ms, warm_kernel_ms = prewarm(kv, torch, step_on, min_ms=args.prewarm_ms) if args.prewarm_ms > 0 else (0.0, 0.0)
     log(f"[bench] pre-warm: {warm_ms:.0f} ms of kernel time until the duration settled at {warm_kernel_ms:.4f} ms")
     ms, main_ms, main_ms_median = timed_steps(kv, torch, step_on, args.steps, args.warmup)
     value = kvb / (ms * 1e-3) / 1e9
@@ -498,6 +579,7 @@ def main():
                    "waves_per_cu": (kv.kv_decode_get_waves_per_cu_kv8(pd_on, cfg["d"]) if args.kv8 else
                                     kv.kv_decode_get_waves_per_cu_for(pd_on, cfg["d"], cfg["Hq"] // cfg["Hkv"])),
                    "prewarm_ms": warm_ms,
+                   **({"fetch_policy": "plain"} if args.fetch_policy == "plain" else {}),
                    **({"l2_touch_tiles": args.l2_touch} if args.l2_touch and pd_on == 0 and not args.kv8 else {}),
                    **({"variant": "two-phase"} if args.two_phase and not args.kv8 else {})},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,

@@ -68,13 +68,16 @@ typedef struct kv_tensor {
  *                MB * block_size.  Cache slots at t >= n_b are never used.
  *   out          [B, Hq, d] same dtype as q, last stride 1, rounded to nearest even.
  *   scale        multiplies the logits (1/sqrt(d) in the tests).
- *   prefetch_distance  0 .. KV_MAX_PREFETCH_DISTANCE.
+ *   prefetch_distance  0 .. KV_MAX_PREFETCH_DISTANCE, or KV_PREFETCH_AUTO.
  *   stream       hipStream_t, NULL = the default stream.
  *
  * Supported: d in {64, 128}, block_size in {16, 32}, Hq/Hkv in 1..16.  Every call needs the
  * registered workspace below.
  */
 #define KV_MAX_PREFETCH_DISTANCE 4
+/* prefetch_distance value that lets the library choose: the distance (and the occupancy that goes with it) measured
+ * fastest on this chip for the cache type: 2 for 16-bit caches, 0 for kv_decode_attn_kv8. */
+#define KV_PREFETCH_AUTO (-1)
 int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
                    const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
                    float scale, int num_kv_heads, int block_size, int prefetch_distance,
@@ -240,6 +243,18 @@ int kv_decode_set_variant(int variant);
 int kv_decode_set_l2_touch(int tiles);
 
 /*
+ * Comparison mode for the cache-policy study (the paper's remark on the eviction priority of prefetched
+ * data, Section 3.3): KV_FETCH_NON_TEMPORAL (default) marks every KV fetch, and every weight load of the
+ * layer stack's dense layer in operand order, non-temporal: the data is used once and should not displace
+ * anything in L2 or the memory-side cache.  KV_FETCH_PLAIN drops the hint, as the "before" of that
+ * comparison; it is built for the benchmark shapes only (kv_decode_attn on bf16, head_dim 128,
+ * prefetch_distance 0 or 2, one-pass variant; dense layer with K = 4096), other calls return
+ * KV_ERR_UNSUPPORTED while it is set.  Results do not depend on it.
+ */
+enum { KV_FETCH_NON_TEMPORAL = 0, KV_FETCH_PLAIN = 1 };
+int kv_decode_set_fetch_policy(int policy);
+
+/*
  * Skew of the workers' shares of the tile space between the even and the odd XCD of every XCD
  * pair, in 1/1024: worker w gets 1024 + skew parts when w is even and 1024 - skew when it is odd
  * (workgroups go to the XCDs round-robin; under load the odd XCD of a pair delivers about 3 % less
@@ -270,7 +285,10 @@ int kv_profile_read_each(float* main_ms, int capacity, int* calls);
  * account).  While device memory is registered here, every persistent worker w of a launch with
  * at most bytes / 32 workers writes four 64-bit words at dev_ptr + 32 w: the constant 100 MHz
  * clock at entry, after it has located its range, at exit, and a word whose low 32 bits are the
- * number of tiles it processed and whose high 32 bits are the XCD (XCC_ID) it ran on.
+ * number of tiles it processed, whose bits 32..35 are the XCD (XCC_ID) it ran on and whose bits
+ * 40..55 are the time from "range located" until its first tile pair had landed, in clock ticks of
+ * 10 ns (saturating; kv_decode_attn's one-pass kernel only, zero elsewhere): the latency the
+ * cross-layer touch of the layer stack is meant to shorten.
  * NULL/0 unregisters.  The caller owns the memory and reads it after synchronising;
  * launches with more workers than fit leave it untouched.  Costs two clock reads per worker.
  */

@@ -43,7 +43,7 @@ class KVTensor(ctypes.Structure):
 EXPORTS = [
     "kv_decode_attn", "kv_decode_attn_noalloc", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
     "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew", "kv_decode_fetch_probe",
-    "kv_decode_set_l2_touch", "kv_decode_set_variant", "kv_decode_get_waves_per_cu_for",
+    "kv_decode_set_l2_touch", "kv_decode_set_variant", "kv_decode_set_fetch_policy", "kv_decode_get_waves_per_cu_for",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
     "kv_block_bytes", "kv_iter_working_set_bytes", "kv_worker_range", "kv_worker_of_tile", "kv_profile_enable", "kv_profile_read", "kv_profile_read_each",
 ]
@@ -263,6 +263,12 @@ def kv_decode_attn_kv8(q, k_cache, v_cache, block_tables, context_lens, out, sca
 
 
 KV_VARIANT_ONE_PASS, KV_VARIANT_TWO_PHASE = 0, 1
+KV_FETCH_NON_TEMPORAL, KV_FETCH_PLAIN = 0, 1
+KV_PREFETCH_AUTO = -1
+
+
+def kv_decode_set_fetch_policy(policy: int):
+    _check(load_library().kv_decode_set_fetch_policy(int(policy)))
 
 
 def kv_decode_set_variant(variant: int):

@@ -54,7 +54,10 @@ namespace kvp {
 // the consumer wave, in groups of p.l2_touch tiles, never more than two groups ahead (the consumer publishes
 // its tile count in LDS; the toucher's only wait is on that count, the consumer never waits for the toucher).
 // The consumer runs the PD = 0 flow (fetch, wait, compute) and finds its lines in L2.
-template <Elem E, int D, int BS, int PD, bool FETCH_ONLY = false, bool TOUCH = false>
+//
+// AUX: cache-policy operand of the KV fetches.  Non-temporal in every shipped path; the plain form exists for the
+// benchmark shapes only, as the "before" of the cache-policy comparison (kv_decode_set_fetch_policy).
+template <Elem E, int D, int BS, int PD, bool FETCH_ONLY = false, bool TOUCH = false, int AUX = kAuxNonTemporal>
 __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_kernel(AttnParams p) {
     static_assert(!TOUCH || (PD == 0 && !FETCH_ONLY), "the L2 touch wave accompanies the flow without LDS look-ahead");
     using G_ = Geo<D>;
@@ -198,10 +201,10 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
         // 184 -> 164 us on the Llama-3-8B-shaped batch
 #pragma unroll
         for (int r = 0; r < LPT; ++r)
-            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(kt + koff[r]), KVP_LDS(dst + r * 1024), 16, 0, kAuxNonTemporal);
+            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(kt + koff[r]), KVP_LDS(dst + r * 1024), 16, 0, AUX);
 #pragma unroll
         for (int r = 0; r < LPT; ++r)
-            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kTileBytes + r * 1024), 16, 0, kAuxNonTemporal);
+            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(vt_ + voff[r]), KVP_LDS(dst + kTileBytes + r * 1024), 16, 0, AUX);
     };
 
     float4v o[CB];
@@ -225,6 +228,7 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
     int stage = 0;
     int piece_first_j = ca.j;                     // where the current piece of the current unit began
     bool piece_at_range_start = true;
+    unsigned long long t_first = 0;               // traced: clock when the first tile pair of the range had landed
     for (int64_t r = r0; r < r1; ++r) {
         if constexpr (TOUCH) {
             if (lane == 0) *progress = (uint32_t)(r - r0 + 1);
@@ -244,6 +248,7 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
             }
         }
         asm volatile("" ::: "memory");
+        if (traced && r == r0) t_first = wall_clock64();
         if constexpr (FETCH_ONLY) {
             if constexpr (PD > 0) { stage = stage + 1 == NS ? 0 : stage + 1; }
             continue;
@@ -351,7 +356,8 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
     if (traced && lane == 0) {
         unsigned long long* t = p.worker_trace + (int64_t)worker * 4;
         t[0] = t_entry; t[1] = t_scan; t[2] = wall_clock64();
-        t[3] = (unsigned long long)(r1 - r0) | ((unsigned long long)xcc_id() << 32);
+        const unsigned long long first_wait = min(t_first - t_scan, 0xffffULL);      // 10 ns ticks from range located to first tile landed
+        t[3] = (unsigned long long)(r1 - r0) | ((unsigned long long)xcc_id() << 32) | (first_wait << 40);
     }
 }
 
@@ -462,6 +468,15 @@ __global__ __launch_bounds__(256) void attn_finalize_kernel(AttnParams p, int bs
 template <Elem E, int D, int BS, int PD>
 static int launch_one(const AttnParams& p, hipStream_t stream) {
     const size_t lds = (size_t)mfma_worker_lds_bytes(PD, D);
+    if (p.plain_fetch) {            // comparison mode: instantiated for the benchmark shapes only
+        if constexpr (E == Elem::BF16 && D == 128 && (PD == 0 || PD == 2)) {
+            auto kern = attn_mfma_kernel<E, D, BS, PD, false, false, 0>;
+            hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), lds, stream, p);
+            return 0;
+        } else {
+            return -1;
+        }
+    }
     auto kern = attn_mfma_kernel<E, D, BS, PD>;
     hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), lds, stream, p);
     return 0;

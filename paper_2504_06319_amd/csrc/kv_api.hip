@@ -53,6 +53,7 @@ size_t g_trace_bytes = 0;
 std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
 std::atomic<int> g_variant{KV_VARIANT_ONE_PASS};   // kernel form of kv_decode_attn on 16-bit caches
 std::atomic<int> g_l2_touch{0};      // tiles per group of the L2 touch wave (0 = none); calls with prefetch_distance 0 only
+std::atomic<int> g_plain_fetch{0};   // comparison mode: KV fetches and dense-layer weight loads without the non-temporal hint
 std::atomic<int> g_xcd_skew{20};     // per 1024: even workers get 1024 + 20 parts of the tile space, odd ones 1024 - 20
 using kvp::kMaxDevices;
 std::atomic<int> g_num_cus[kMaxDevices];   // compute units per device ordinal, read once each (0 = not read yet)
@@ -172,8 +173,12 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
         return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: block_size %d not in {16,32}", block_size);
     const int G = (int)(Hq / num_kv_heads);
     if (G > 16) return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: %d query heads per kv head exceeds 16", G);
+    // KV_PREFETCH_AUTO: the distance measured best for the cache type, at the occupancy that goes with it (16-bit
+    // caches: two tiles ahead with two waves per compute unit; 8-bit caches need six waves for their arithmetic, and
+    // six waves' own requests already fill the memory system: no look-ahead)
+    if (prefetch_distance == KV_PREFETCH_AUTO) prefetch_distance = kv8 ? 0 : 2;
     if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE)
-        return fail(KV_ERR_INVALID, "kv_decode_attn: prefetch_distance %d outside 0..%d", prefetch_distance, KV_MAX_PREFETCH_DISTANCE);
+        return fail(KV_ERR_INVALID, "kv_decode_attn: prefetch_distance %d outside 0..%d (or KV_PREFETCH_AUTO)", prefetch_distance, KV_MAX_PREFETCH_DISTANCE);
     // 128-bit loads need 16-byte aligned rows
     auto aligned = [](const kv_tensor* t, int nstr, int elems_per_16_bytes) {
         if (((uintptr_t)t->data) % 16) return false;
@@ -208,7 +213,8 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     const int nw = cus * waves_per_cu(prefetch_distance, (int)d, kv8, r->two_phase ? G : 0);
     p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
     p.xcd_skew = g_xcd_skew.load();
-    p.l2_touch = (!kv8 && !r->two_phase && prefetch_distance == 0) ? g_l2_touch.load() : 0;
+    p.plain_fetch = (!kv8 && !r->two_phase) ? g_plain_fetch.load() : 0;
+    p.l2_touch = (!kv8 && !r->two_phase && prefetch_distance == 0 && !p.plain_fetch) ? g_l2_touch.load() : 0;
     r->partial_bytes = kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
     p.partials = nullptr;           // bound by bind_registered / bind_static
     p.worker_trace = nullptr;
@@ -314,7 +320,8 @@ int run_attn(const Resolved& r, hipStream_t stream) {
                          : r.p.l2_touch ? kvp::launch_attn_l2_touch(r.p, r.elem, r.d, r.bs, stream)
                                         : kvp::launch_attn_mfma(r.p, r.elem, r.d, r.bs, stream);
     if (launched != 0)
-        return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d", r.d, r.bs, r.p.G);
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: no kernel for head_dim %d, block_size %d, group %d%s", r.d, r.bs, r.p.G,
+                    r.p.plain_fetch ? " under KV_FETCH_PLAIN (bf16, head_dim 128, distance 0 or 2 only)" : "");
     if (int rc = check_launch("kv_decode_attn main kernel")) return rc;
     if (slot >= 0) (void)hipEventRecord(prof_event(slot, 1), stream);
     kvp::launch_finalize_mfma(r.p, r.elem, r.d, r.bs, stream);
@@ -497,7 +504,8 @@ int kv_decode_layerstack(int num_layers, const kv_tensor* x, const kv_tensor* co
         int grc;
         if (wl->ndim == 5) {
             grc = kvp::launch_layer_gemm_packed(x->data, wl->data, gemm_out->data, (int)M, (int)K, (int)N, x->stride[0],
-                                                gemm_out->stride[0], gemm_tickets, gemm_partials, main_stream);
+                                                gemm_out->stride[0], gemm_tickets, gemm_partials, g_plain_fetch.load() != 0,
+                                                main_stream);
         } else {
             const int64_t ldw = wl->ndim == 2 ? wl->stride[0] : wl->stride[1];
             const int64_t w_tile_stride = wl->ndim == 2 ? 128 : wl->stride[0];
@@ -568,6 +576,13 @@ int kv_decode_set_variant(int variant) {
 int kv_decode_set_l2_touch(int tiles) {
     if (tiles < 0 || tiles > 8) return fail(KV_ERR_INVALID, "kv_decode_set_l2_touch: %d outside 0..8", tiles);
     g_l2_touch.store(tiles);
+    return KV_OK;
+}
+
+int kv_decode_set_fetch_policy(int policy) {
+    if (policy != KV_FETCH_NON_TEMPORAL && policy != KV_FETCH_PLAIN)
+        return fail(KV_ERR_INVALID, "kv_decode_set_fetch_policy: unknown policy %d", policy);
+    g_plain_fetch.store(policy == KV_FETCH_PLAIN ? 1 : 0);
     return KV_OK;
 }
 

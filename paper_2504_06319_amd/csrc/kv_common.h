@@ -35,6 +35,7 @@ struct AttnParams {
     int32_t tile_shift;       // log2 of the tokens per tile of the flat tile space: 4 (16-bit caches) or 5 (8-bit)
     int32_t l2_touch;         // > 0 with prefetch_distance 0: a second wave per worker touches this many tiles per group into L2
     int32_t xcd_skew;         // per-1024 skew of the range sizes between even and odd workers (XCDs)
+    int32_t plain_fetch;      // comparison mode: KV fetches without the non-temporal hint (benchmark shapes only)
     float scale_log2e;        // scale * log2(e) (* k_scale for an 8-bit cache): logits live in the base-2 domain
     float out_scale;          // multiplies every output row: 1, or v_scale for an 8-bit cache
 };
@@ -64,7 +65,7 @@ int launch_touch_mfma(const AttnParams& p, int d, int bs, int tiles, uint32_t* s
 int launch_layer_gemm(const void* x, const void* w, void* y, int M, int K, int N, int64_t ldx, int64_t ldw,
                       int64_t w_tile_stride, int64_t ldy, hipStream_t stream);
 int launch_layer_gemm_packed(const void* x, const void* wp, void* y, int M, int K, int N, int64_t ldx, int64_t ldy,
-                             int* tickets, float* partials, hipStream_t stream);
+                             int* tickets, float* partials, bool plain_fetch, hipStream_t stream);
 size_t layer_gemm_packed_partial_bytes(int N);
 void launch_zero_words(int* p, int n, hipStream_t stream);
 constexpr size_t kGemmTicketBytes = 4096;      // head of the workspace: one ticket word per 128-column tile of the dense layer

@@ -93,9 +93,13 @@ struct PkSchedule {
 
 // 16 bytes per lane from (wave-uniform base in scalar registers) + (lane byte offset) + OFF; non-temporal: W is
 // read once per pass
-template <int OFF>
+// (PLAIN: without the hint, the "before" of the cache-policy comparison)
+template <int OFF, bool PLAIN>
 __device__ __forceinline__ void pk_load_w(pk_u4& dst, const unsigned char* base, uint32_t lane_off) {
-    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(dst) : "v"(lane_off), "s"(base), "n"(OFF) : "memory");
+    if constexpr (PLAIN)
+        asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(lane_off), "s"(base), "n"(OFF) : "memory");
+    else
+        asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(dst) : "v"(lane_off), "s"(base), "n"(OFF) : "memory");
 }
 
 template <class F, int... I>
@@ -133,7 +137,7 @@ __device__ __forceinline__ void pk_wait_a(pk_u4 (&a)[8]) {
 // STEPS = k-steps per workgroup: K = 2 halves * STEPS * 32.
 // tickets: one word per column tile, zero before the first launch; partials: per column tile two fp32 tiles of
 // 128 x 128 in register order.
-template <int STEPS>
+template <int STEPS, bool PLAIN = false>
 __global__ __launch_bounds__(256) void layer_gemm_packed_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wp,
                                                                 uint16_t* __restrict__ y, int M, int N, int64_t ldx,
                                                                 int64_t ldy, int* tickets, float* partials) {
@@ -168,7 +172,7 @@ __global__ __launch_bounds__(256) void layer_gemm_packed_kernel(const uint16_t* 
     const uint32_t w_lane = lane * 16;
     auto load_w = [&](pk_u4 (&slot)[kPkWOwn], int kstep, auto nb_tag) {
         constexpr int nb = decltype(nb_tag)::value;
-        pk_load_w<nb * 1024>(slot[nb], wg + (int64_t)kstep * 4096, w_lane);
+        pk_load_w<nb * 1024, PLAIN>(slot[nb], wg + (int64_t)kstep * 4096, w_lane);
     };
     // A operand of m-block mb: row 16 mb + lr, logical chunk lq -> stored chunk lq ^ (lr / 4) % 4; + 1024 per m-block
     const uint32_t a_off = lr * 64 + ((lq ^ ((lr / 4) % 4)) << 4);
@@ -284,10 +288,10 @@ __global__ __launch_bounds__(256) void layer_gemm_packed_kernel(const uint16_t* 
             }
 }
 
-template <int STEPS>
+template <int STEPS, bool PLAIN = false>
 static int launch_packed(const void* x, const void* wp, void* y, int M, int N, int64_t ldx, int64_t ldy, int* tickets,
                          float* partials, hipStream_t stream) {
-    auto kern = layer_gemm_packed_kernel<STEPS>;
+    auto kern = layer_gemm_packed_kernel<STEPS, PLAIN>;
     static LdsLimit limit;
     if (limit.raise(reinterpret_cast<const void*>(kern), kPkLds) != 0) return -2;
     const int tiles = N / kPkBN;
@@ -316,9 +320,11 @@ size_t layer_gemm_packed_partial_bytes(int N) {
 // before the first launch, `partials` layer_gemm_packed_partial_bytes(N).  Returns 0, -1 (shape not covered: K must
 // be 1024, 2048, 4096 or 8192, N a multiple of 128 up to 128 * 1024) or -2 (HIP refused the LDS size).
 int launch_layer_gemm_packed(const void* x, const void* wp, void* y, int M, int K, int N, int64_t ldx, int64_t ldy,
-                             int* tickets, float* partials, hipStream_t stream) {
+                             int* tickets, float* partials, bool plain_fetch, hipStream_t stream) {
     if (M < 1 || M > kPkBM || N < kPkBN || N % kPkBN || N / kPkBN > (int)(kGemmTicketBytes / sizeof(int))) return -1;
     if ((int64_t)kPkBM * ldx * 2 + 64 > 0x7fffffffLL) return -1;      // x byte offsets are kept in 32 bits
+    if (plain_fetch)            // comparison mode: the benchmark's K only
+        return K == 4096 ? launch_packed<64, true>(x, wp, y, M, N, ldx, ldy, tickets, partials, stream) : -1;
     switch (K) {
         case 1024: return launch_packed<16>(x, wp, y, M, N, ldx, ldy, tickets, partials, stream);
         case 2048: return launch_packed<32>(x, wp, y, M, N, ldx, ldy, tickets, partials, stream);

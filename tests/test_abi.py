@@ -121,7 +121,7 @@ def test_invalid_arguments_are_rejected_before_launch(mutate, status, needle):
 
 def test_scalar_arguments_are_checked():
     a = _good()
-    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], pd=-1) == 1
+    assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], pd=-2) == 1      # -1 is KV_PREFETCH_AUTO
     assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], pd=kv.KV_MAX_PREFETCH_DISTANCE + 1) == 1
     assert _call(a["q"], a["k"], a["v"], a["bt"], a["cl"], a["out"], hkv=0) == 1
     f = torch.bfloat16
@@ -191,6 +191,12 @@ def test_l2_touch_range_is_checked():
     lib = kv.load_library()
     assert lib.kv_decode_set_l2_touch(-1) == 1 and lib.kv_decode_set_l2_touch(9) == 1
     assert lib.kv_decode_set_l2_touch(4) == 0 and lib.kv_decode_set_l2_touch(0) == 0
+
+
+def test_fetch_policy_is_checked():
+    lib = kv.load_library()
+    assert lib.kv_decode_set_fetch_policy(2) == 1 and lib.kv_decode_set_fetch_policy(-1) == 1
+    assert lib.kv_decode_set_fetch_policy(kv.KV_FETCH_PLAIN) == 0 and lib.kv_decode_set_fetch_policy(kv.KV_FETCH_NON_TEMPORAL) == 0
 
 
 def test_xcd_skew_range_is_checked():

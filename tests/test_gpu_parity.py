@@ -386,6 +386,45 @@ def test_l2_touch_wave_on_a_full_size_configuration():
         kv.kv_decode_set_waves_per_cu(0)
 
 
+def test_automatic_prefetch_distance_is_the_measured_best_one():
+    """KV_PREFETCH_AUTO resolves to distance 2 on a 16-bit cache and to distance 0 on an 8-bit one: the bits of those
+    explicit calls."""
+    cfg = _cfg(8, 2, 128, 16, "bf16")
+    lens = [900, 0, 17, 2500, 64, 1]
+    c = synth.make_case(cfg, 311, DEV, poison=True, lens=lens)
+    assert torch.equal(run_hip(c, kv.KV_PREFETCH_AUTO).view(torch.int16), run_hip(c, 2).view(torch.int16))
+    c8 = synth.make_case_kv8(cfg, 311, DEV, poison=True, lens=lens, k_scale=0.5, v_scale=2.0)
+    outs = []
+    for pd in (kv.KV_PREFETCH_AUTO, 0):
+        out = torch.full_like(c8["q"], float("nan"))
+        kv.kv_decode_attn_kv8(c8["q"], c8["k_cache"], c8["v_cache"], c8["block_tables"], c8["context_lens"], out, c8["scale"],
+                              c8["k_scale"], c8["v_scale"], 2, 16, pd)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+    with pytest.raises(kv.KVError):
+        run_hip(c, -2)
+
+
+def test_fetches_without_the_non_temporal_hint_change_no_bit():
+    """The cache-policy comparison mode (plain KV fetches) is built for the benchmark shapes: same bits as the default,
+    and a clear refusal for shapes it was not built for."""
+    c = synth.make_case(_cfg(32, 8, 128, 16, "bf16"), 313, DEV, poison=True, lens=[3000, 0, 17, 700, 8192, 1])
+    small = synth.make_case(_cfg(4, 4, 64, 16, "f16"), 314, DEV, lens=[100, 30])
+    want = {pd: run_hip(c, pd) for pd in (0, 2)}
+    kv.kv_decode_set_fetch_policy(kv.KV_FETCH_PLAIN)
+    try:
+        for pd in (0, 2):
+            assert torch.equal(run_hip(c, pd).view(torch.int16), want[pd].view(torch.int16)), f"distance {pd}"
+        for case, pd in ((c, 1), (small, 2)):
+            with pytest.raises(kv.KVError) as e:
+                run_hip(case, pd)
+            assert e.value.status == 2 and "KV_FETCH_PLAIN" in str(e.value)
+    finally:
+        kv.kv_decode_set_fetch_policy(kv.KV_FETCH_NON_TEMPORAL)
+    compare(run_hip(small, 2), run_oracle(small), "default policy again")
+
+
 def test_worker_timeline_accounts_for_every_tile():
     """Every worker reports its entry / range-located / exit clock readings and its tile count: the counts add
     up to the tiles of the batch (per kv head), the readings are ordered, and the result is unchanged."""
@@ -401,7 +440,9 @@ def test_worker_timeline_accounts_for_every_tile():
         kv.kv_decode_set_worker_trace(None)
     t = trace.cpu().numpy()
     active = t[t[:, 3] > 0]
-    xcd, active[:, 3] = active[:, 3] >> 32, active[:, 3] & 0xffffffff
+    first_wait = (active[:, 3] >> 40) & 0xffff
+    xcd, active[:, 3] = (active[:, 3] >> 32) & 0xf, active[:, 3] & 0xffffffff
+    assert (first_wait > 0).all() and (first_wait < 0xffff).all()      # the first tile pair took between 10 ns and 0.65 ms
     assert ((xcd >= 0) & (xcd < 8)).all()
     tiles = sum((n + 15) // 16 for n in lens) * cfg["Hkv"]
     assert active[:, 3].sum() == tiles
