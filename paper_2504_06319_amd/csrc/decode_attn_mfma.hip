@@ -374,9 +374,12 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
 // per thread; the kernel is a chain of dependent memory round trips, so it is written to have few of them: the
 // scan of context_lens, then every load of a batch of 32 / IT pieces (max, sum and accumulator column) in flight
 // at once, each thread keeping its running (m*, sum, acc) across batches.
+// Every wave of a workgroup repeats the scan, so the workgroup is as small as the launch allows: one wave when
+// units are cut into few pieces (many units per worker: up to 8 pairs per thread, 4 pieces per batch), four
+// waves when few long units are cut into many pieces each (few pairs per thread, up to 32 pieces per batch).
 // Empty sequences: workgroup w writes the zero rows of sequences w, w + gridDim.x, ...
-template <Elem E, int D, int IT>
-__global__ __launch_bounds__(256) void attn_finalize_kernel(AttnParams p, int bs) {
+template <Elem E, int D, int IT, int THREADS>
+__global__ __launch_bounds__(THREADS) void attn_finalize_kernel(AttnParams p, int bs) {
     constexpr int PS = Geo<D>::kPartialStride;
     constexpr int U = 32 / IT;                          // pieces per batch
     const int w = blockIdx.x, tid = threadIdx.x, lane = tid % kWaveSize;
@@ -387,7 +390,7 @@ __global__ __launch_bounds__(256) void attn_finalize_kernel(AttnParams p, int bs
     for (int b = w; b < p.B; b += gridDim.x) {          // zero rows of empty contexts
         if (tiles_of(clamp_len(cl[b], max_len), p.tile_shift) != 0) continue;
         uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + (int64_t)b * p.out_stride_b;
-        for (int idx = tid; idx < p.Hq * D; idx += 256) orow[(int64_t)(idx / D) * p.out_stride_h + idx % D] = 0;
+        for (int idx = tid; idx < p.Hq * D; idx += THREADS) orow[(int64_t)(idx / D) * p.out_stride_h + idx % D] = 0;
     }
 
     const int total = scan_total(cl, p.B, max_len, lane, p.tile_shift);
@@ -407,14 +410,14 @@ __global__ __launch_bounds__(256) void attn_finalize_kernel(AttnParams p, int bs
     const int np = w1 - w + 1;
     const int slot_first = a > r0 ? 1 : 0;
 
-    // this thread's (head, column) pairs: idx = tid + 256 k < G * D
+    // this thread's (head, column) pairs: idx = tid + THREADS k < G * D
     const float* first_row[IT];
     const float* later_rows[IT];                        // + i * 2 * G * PS for piece i >= 1
     int col[IT];
     bool live[IT];
 #pragma unroll
     for (int k = 0; k < IT; ++k) {
-        const int idx = tid + 256 * k;
+        const int idx = tid + THREADS * k;
         live[k] = idx < G * D;
         const int g = live[k] ? idx / D : 0;
         col[k] = idx % D;
@@ -460,7 +463,7 @@ __global__ __launch_bounds__(256) void attn_finalize_kernel(AttnParams p, int bs
 #pragma unroll
     for (int k = 0; k < IT; ++k) {
         if (!live[k]) continue;
-        const int g = (tid + 256 * k) / D;
+        const int g = (tid + THREADS * k) / D;
         obase[(int64_t)(kvh * G + g) * p.out_stride_h + col[k]] = pack1<E>(num[k] / den[k] * p.out_scale);
     }
 }
@@ -560,14 +563,29 @@ size_t mfma_partial_bytes(int num_workers, int G, int d) {
 
 // Merge kernel; always launched after the main kernel (it also writes the zero rows of empty sequences): one
 // workgroup per worker of the main launch.
+template <Elem E, int D, int IT, int THREADS>
+static void launch_finalize_shape(const AttnParams& p, int bs, hipStream_t stream) {
+    hipLaunchKernelGGL((attn_finalize_kernel<E, D, IT, THREADS>), dim3(p.num_workers), dim3(THREADS), 0, stream, p, bs);
+}
+
 template <Elem E, int D>
 static void launch_finalize_it(const AttnParams& p, int bs, hipStream_t stream) {
-    const dim3 grid(p.num_workers), block(256);
-    const int pairs = p.G * D;                      // (head, column) pairs of a unit, 256 threads
-    if (pairs <= 256) hipLaunchKernelGGL((attn_finalize_kernel<E, D, 1>), grid, block, 0, stream, p, bs);
-    else if (pairs <= 512) hipLaunchKernelGGL((attn_finalize_kernel<E, D, 2>), grid, block, 0, stream, p, bs);
-    else if (pairs <= 1024) hipLaunchKernelGGL((attn_finalize_kernel<E, D, 4>), grid, block, 0, stream, p, bs);
-    else hipLaunchKernelGGL((attn_finalize_kernel<E, D, 8>), grid, block, 0, stream, p, bs);
+    const int pairs = p.G * D;                      // (head, column) pairs of a unit
+    // a cut unit has about workers / units + 1 pieces: few (one batch of four) when there are at least a quarter as
+    // many units as workers
+    const bool few_pieces = 4 * (int64_t)p.B * p.Hkv >= p.num_workers;
+    if (few_pieces) {
+        if (pairs <= 64) return launch_finalize_shape<E, D, 1, 64>(p, bs, stream);
+        if (pairs <= 128) return launch_finalize_shape<E, D, 2, 64>(p, bs, stream);
+        if (pairs <= 256) return launch_finalize_shape<E, D, 4, 64>(p, bs, stream);
+        if (pairs <= 512) return launch_finalize_shape<E, D, 8, 64>(p, bs, stream);
+        if (pairs <= 1024) return launch_finalize_shape<E, D, 8, 128>(p, bs, stream);
+        return launch_finalize_shape<E, D, 8, 256>(p, bs, stream);
+    }
+    if (pairs <= 256) return launch_finalize_shape<E, D, 1, 256>(p, bs, stream);
+    if (pairs <= 512) return launch_finalize_shape<E, D, 2, 256>(p, bs, stream);
+    if (pairs <= 1024) return launch_finalize_shape<E, D, 4, 256>(p, bs, stream);
+    return launch_finalize_shape<E, D, 8, 256>(p, bs, stream);
 }
 
 int launch_finalize_mfma(const AttnParams& p, int elem, int d, int bs, hipStream_t stream) {
