@@ -258,7 +258,7 @@ int kv_decode_set_fetch_policy(int policy);
  * Skew of the workers' shares of the tile space between the even and the odd XCD of every XCD
  * pair, in 1/1024: worker w gets 1024 + skew parts when w is even and 1024 - skew when it is odd
  * (workgroups go to the XCDs round-robin; under load the odd XCD of a pair delivers about 3 % less
- * bandwidth).  0 gives equal shares; 0 .. 256; default 20.  Results depend on it only through
+ * bandwidth).  0 gives equal shares; 0 .. 256; default 10.  Results depend on it only through
  * where units are cut (rounding of the merge), like on the worker count.
  */
 int kv_decode_set_xcd_skew(int per_1024);

@@ -54,7 +54,7 @@ std::atomic<int> g_waves_per_cu{0};  // 0 = automatic
 std::atomic<int> g_variant{KV_VARIANT_ONE_PASS};   // kernel form of kv_decode_attn on 16-bit caches
 std::atomic<int> g_l2_touch{0};      // tiles per group of the L2 touch wave (0 = none); calls with prefetch_distance 0 only
 std::atomic<int> g_plain_fetch{0};   // comparison mode: KV fetches and dense-layer weight loads without the non-temporal hint
-std::atomic<int> g_xcd_skew{20};     // per 1024: even workers get 1024 + 20 parts of the tile space, odd ones 1024 - 20
+std::atomic<int> g_xcd_skew{10};     // per 1024: even workers get 1024 + 10 parts of the tile space, odd ones 1024 - 10
 using kvp::kMaxDevices;
 std::atomic<int> g_num_cus[kMaxDevices];   // compute units per device ordinal, read once each (0 = not read yet)
 

@@ -202,7 +202,7 @@ def test_fetch_policy_is_checked():
 def test_xcd_skew_range_is_checked():
     lib = kv.load_library()
     assert lib.kv_decode_set_xcd_skew(-1) == 1 and lib.kv_decode_set_xcd_skew(257) == 1
-    assert lib.kv_decode_set_xcd_skew(0) == 0 and lib.kv_decode_set_xcd_skew(20) == 0
+    assert lib.kv_decode_set_xcd_skew(0) == 0 and lib.kv_decode_set_xcd_skew(10) == 0
 
 
 def test_operand_order_packing_places_every_element():

@@ -170,7 +170,7 @@ def test_skewed_shares_of_even_and_odd_workers(skew):
         got = run_hip(c, 2)
     finally:
         kv.kv_decode_set_worker_trace(None)
-        kv.kv_decode_set_xcd_skew(20)
+        kv.kv_decode_set_xcd_skew(10)
         kv.kv_decode_set_waves_per_cu(0)
     compare(got, run_oracle(c), f"skew={skew}")
     tiles = trace.cpu().numpy()[:256, 3] & 0xffffffff
