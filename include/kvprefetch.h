@@ -84,6 +84,18 @@ int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor
                    void* stream);
 
 /*
+ * Debugging aid, not for the hot path: the attention calls cannot report bad DATA (that would need
+ * a synchronisation), they clamp instead.  This call waits for `stream`, copies block_tables and
+ * context_lens to the host and checks what the kernels would otherwise clamp silently: every
+ * context length in 0 .. MB * block_size, and every block id a sequence actually uses (entries
+ * [b, 0 .. ceil(n_b / block_size) - 1]; the rest of a row may hold anything) in 0 .. num_blocks - 1.
+ * KV_OK, or KV_ERR_INVALID with the first offending entry named in kv_last_error().  Allocates host
+ * memory.
+ */
+int kv_validate_inputs(const kv_tensor* block_tables, const kv_tensor* context_lens, int num_blocks,
+                       int block_size, void* stream);
+
+/*
  * Measurement aid: the fetch stream of kv_decode_attn with the arithmetic left out.  Same
  * arguments and checks, same worker ranges, block-table lookups and asynchronous tile fetches at
  * the same prefetch_distance and occupancy; nothing is read back from LDS and nothing is written

@@ -41,7 +41,7 @@ class KVTensor(ctypes.Structure):
 
 
 EXPORTS = [
-    "kv_decode_attn", "kv_decode_attn_noalloc", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
+    "kv_decode_attn", "kv_decode_attn_noalloc", "kv_validate_inputs", "kv_decode_attn_kv8", "kv_decode_get_waves_per_cu_kv8", "kv_decode_layerstack", "kv_decode_workspace_bytes", "kv_layerstack_workspace_bytes",
     "kv_decode_set_workspace", "kv_decode_set_worker_trace", "kv_decode_set_xcd_skew", "kv_decode_fetch_probe",
     "kv_decode_set_l2_touch", "kv_decode_set_variant", "kv_decode_set_fetch_policy", "kv_decode_get_waves_per_cu_for",
     "kv_decode_set_waves_per_cu", "kv_decode_get_waves_per_cu", "kv_last_error", "kv_version",
@@ -69,6 +69,8 @@ def load_library():
                                            ctypes.c_int, ctypes.c_void_p]
             lib.kv_decode_attn_noalloc.restype = ctypes.c_int
             lib.kv_decode_attn_noalloc.argtypes = lib.kv_decode_attn.argtypes
+            lib.kv_validate_inputs.restype = ctypes.c_int
+            lib.kv_validate_inputs.argtypes = [T, T, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
             lib.kv_decode_fetch_probe.restype = ctypes.c_int
             lib.kv_decode_fetch_probe.argtypes = lib.kv_decode_attn.argtypes
             lib.kv_decode_attn_kv8.restype = ctypes.c_int
@@ -232,6 +234,13 @@ def kv_decode_attn_noalloc(q, k_cache, v_cache, block_tables, context_lens, out,
     _check(lib.kv_decode_attn_noalloc(*[ctypes.byref(d) for d in descs], float(scale), int(num_kv_heads),
                                       int(block_size), int(prefetch_distance), ctypes.c_void_p(_stream_handle(stream))))
     return out
+
+
+def kv_validate_inputs(block_tables, context_lens, num_blocks, block_size, stream=None):
+    """Synchronising check of the lengths and of every block id in use; raises KVError naming the first bad entry."""
+    dbt, dcl = describe(block_tables), describe(context_lens)
+    _check(load_library().kv_validate_inputs(ctypes.byref(dbt), ctypes.byref(dcl), int(num_blocks), int(block_size),
+                                             ctypes.c_void_p(_stream_handle(stream))))
 
 
 def kv_decode_fetch_probe(q, k_cache, v_cache, block_tables, context_lens, out, scale, num_kv_heads,

@@ -549,6 +549,37 @@ int kv_decode_set_workspace(void* dev_ptr, size_t bytes) {
     return KV_OK;
 }
 
+int kv_validate_inputs(const kv_tensor* block_tables, const kv_tensor* context_lens, int num_blocks, int block_size, void* stream) {
+    if (!block_tables || !context_lens || !block_tables->data || !context_lens->data)
+        return fail(KV_ERR_INVALID, "kv_validate_inputs: null tensor");
+    if (block_tables->ndim != 2 || context_lens->ndim != 1 || block_tables->dtype != KV_I32 || context_lens->dtype != KV_I32 ||
+        block_tables->stride[1] != 1 || context_lens->stride[0] != 1 || block_tables->shape[0] != context_lens->shape[0] ||
+        block_tables->shape[0] <= 0 || block_tables->shape[1] <= 0 || block_tables->stride[0] < block_tables->shape[1])
+        return fail(KV_ERR_INVALID, "kv_validate_inputs: block_tables must be int32 [B, MB] with dense rows, context_lens int32 [B], dense");
+    if (num_blocks <= 0 || (block_size != 16 && block_size != 32))
+        return fail(KV_ERR_INVALID, "kv_validate_inputs: num_blocks %d, block_size %d", num_blocks, block_size);
+    const int64_t B = block_tables->shape[0], MB = block_tables->shape[1], ld = block_tables->stride[0];
+    std::vector<int32_t> lens((size_t)B), table((size_t)((B - 1) * ld + MB));
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess) e = hipMemcpy(lens.data(), context_lens->data, lens.size() * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(table.data(), block_tables->data, table.size() * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(KV_ERR_HIP, "kv_validate_inputs: %s", hipGetErrorString(e));
+    for (int64_t b = 0; b < B; ++b) {
+        const int64_t n = lens[(size_t)b];
+        if (n < 0 || n > MB * block_size)
+            return fail(KV_ERR_INVALID, "kv_validate_inputs: context_lens[%lld] = %lld outside 0..%lld (table width x block size)",
+                        (long long)b, (long long)n, (long long)(MB * block_size));
+        const int64_t used = (n + block_size - 1) / block_size;
+        for (int64_t i = 0; i < used; ++i) {
+            const int32_t id = table[(size_t)(b * ld + i)];
+            if (id < 0 || id >= num_blocks)
+                return fail(KV_ERR_INVALID, "kv_validate_inputs: block_tables[%lld, %lld] = %d outside 0..%d", (long long)b, (long long)i,
+                            id, num_blocks - 1);
+        }
+    }
+    return KV_OK;
+}
+
 int kv_decode_set_worker_trace(void* dev_ptr, size_t bytes) {
     if ((dev_ptr == nullptr) != (bytes == 0))
         return fail(KV_ERR_INVALID, "kv_decode_set_worker_trace: pointer and size must both be set or both be zero");

@@ -193,6 +193,16 @@ def test_l2_touch_range_is_checked():
     assert lib.kv_decode_set_l2_touch(4) == 0 and lib.kv_decode_set_l2_touch(0) == 0
 
 
+def test_validate_inputs_checks_its_descriptors_first():
+    lib = kv.load_library()
+    a = _good()
+    ref = ctypes.byref
+    assert lib.kv_validate_inputs(None, None, 10, 16, None) == 1
+    assert lib.kv_validate_inputs(ref(a["bt"]), ref(a["cl"]), 0, 16, None) == 1          # no blocks
+    assert lib.kv_validate_inputs(ref(a["bt"]), ref(a["cl"]), 10, 8, None) == 1          # block size
+    assert lib.kv_validate_inputs(ref(a["q"]), ref(a["cl"]), 10, 16, None) == 1          # not an int32 table
+
+
 def test_fetch_policy_is_checked():
     lib = kv.load_library()
     assert lib.kv_decode_set_fetch_policy(2) == 1 and lib.kv_decode_set_fetch_policy(-1) == 1

@@ -257,6 +257,30 @@ def test_garbage_ids_in_unused_table_entries_are_never_dereferenced():
     compare(run_hip(c, 3), want, "garbage table tail")
 
 
+def test_validate_inputs_names_the_first_bad_entry():
+    """The synchronising checker accepts what the generators make (garbage in unused table entries included) and names
+    the first length or block id the kernels would have clamped."""
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 27, DEV, lens=[40, 513, 0, 16], table_width=40)
+    nblk = c["k_cache"].shape[0]
+    bt = c["block_tables"]
+    for b, n in enumerate(c["lens"]):
+        bt[b, -(-int(n) // 16):] = -7                       # unused entries may hold anything
+    kv.kv_validate_inputs(bt, c["context_lens"], nblk, 16)
+    bad = bt.clone(); bad[1, 3] = nblk
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_validate_inputs(bad, c["context_lens"], nblk, 16)
+    assert e.value.status == 1 and "block_tables[1, 3]" in str(e.value)
+    lens = c["context_lens"].clone(); lens[3] = 40 * 16 + 1
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_validate_inputs(bt, lens, nblk, 16)
+    assert "context_lens[3]" in str(e.value)
+    lens[3] = -1
+    with pytest.raises(kv.KVError):
+        kv.kv_validate_inputs(bt, lens, nblk, 16)
+    with pytest.raises(kv.KVError):
+        kv.kv_validate_inputs(bt.to(torch.int64), c["context_lens"], nblk, 16)
+
+
 def test_permuting_physical_block_ids_changes_nothing():
     c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 29, DEV, lens=[700, 33, 1500])
     a = run_hip(c, 1)
