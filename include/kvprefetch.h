@@ -212,9 +212,10 @@ int kv_decode_attn_noalloc(const kv_tensor* q, const kv_tensor* k_cache, const k
  * Persistent waves (workers) per compute unit, 1 .. 16; 0 restores the automatic choice, which
  * aims at 32-48 KB of KV in flight per compute unit: 6 waves at prefetch distance 0 or 1 and 2
  * waves at distance 2 or more for head_dim 128, 8 and 4 waves for head_dim 64.
- * Each worker holds (prefetch_distance + 1) stages of LDS (8 KB each at head_dim 128, 4 KB at
- * 64), so the number in effect is capped by the 160 KB of a compute unit (Eq. 2 re-derived
- * for LDS as the prefetch target: bytes in flight per CU = stage x prefetch_distance x waves);
+ * Each worker holds (prefetch_distance + 1) stages of LDS (a tile pair of 8 KB and the query image of
+ * a unit, 4 KB, at head_dim 128; 4 KB + 2 KB at 64), so the number in effect is capped by the 160 KB
+ * of a compute unit (Eq. 2 re-derived for LDS as the prefetch target: bytes in flight per CU = tile
+ * pair x prefetch_distance x waves);
  * kv_decode_get_waves_per_cu returns the number a call with that distance and head_dim would use
  * (for the kernel variant in effect, see kv_decode_set_variant).
  */
@@ -224,8 +225,8 @@ int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
  * two-phase variant depends (kv_decode_get_waves_per_cu assumes 16 there); 0 for invalid arguments. */
 int kv_decode_get_waves_per_cu_for(int prefetch_distance, int head_dim, int q_heads_per_kv_head);
 /* The same for kv_decode_attn_kv8 (stages of the same bytes, holding 32 tokens; twice the arithmetic
- * per byte, so more waves: at head_dim 128 6 waves up to distance 2 and 4 beyond, at head_dim 64 12
- * waves at distance 0 and 8 beyond). */
+ * per byte, so more waves: at head_dim 128 6 waves, at head_dim 64 12 waves at distance 0 and 8
+ * beyond, fewer where the LDS caps them, and then an even number). */
 int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
 
 /*

@@ -255,6 +255,7 @@ struct Geo {
     static constexpr int kRowBytes = D * 2;                        // one token's row of K (or V)
     static constexpr int kTileBytes = kTileTokens * kRowBytes;     // 4 KB (d 128) / 2 KB (d 64) for K, the same for V
     static constexpr int kStageBytes = 2 * kTileBytes;
+    static constexpr int kQueryBytes = kTileBytes;                 // a unit's query rows, laid out like a K tile (16 rows)
     static constexpr int kChunks = D / 8;                          // 16-byte chunks per row
     static constexpr int kRowsPerLoad = kWaveSize / kChunks;       // rows one wave-wide 1 KB fetch lands
     static constexpr int kLoadsPerTile = kTileTokens / kRowsPerLoad;

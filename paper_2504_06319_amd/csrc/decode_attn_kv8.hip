@@ -122,30 +122,35 @@ __global__ __launch_bounds__(kWaveSize) void attn_kv8_kernel(AttnParams p) {
         ca.kvh = rem / ca.ntiles;
         ca.j = rem - ca.kvh * ca.ntiles;
     }
-    auto advance = [&](Cursor& c) {              // step to the next flat tile; the caller knows one exists
-        if (++c.j < c.ntiles) return;
+    auto advance = [&](Cursor& c) {              // step to the next flat tile (the caller knows one exists); true when it belongs to another unit
+        if (++c.j < c.ntiles) return false;
         c.j = 0;
-        if (++c.kvh < Hkv) return;
+        if (++c.kvh < Hkv) return true;
         c.kvh = 0;
         do {
             ++c.b;
             c.n = clamp_len(cl[c.b], max_len);
             c.ntiles = tiles_of(c.n, kTileShift8);
         } while (c.ntiles == 0 && c.b + 1 < p.B);
+        return true;
     };
 
-    // ---- Q^T operand of a unit: lane (g = lr, lq) holds Q[g][(4j + lq) * 8 .. +8], zero rows for g >= G
+    // ---- Q^T operand of a unit: lane (g = lr, lq) holds Q[g][(4j + lq) * 8 .. +8], zero rows for g >= G.  As in the
+    // 16-bit kernel the unit's query rows are fetched by global_load_lds into a ring of PD + 1 query images (16 rows of
+    // 16-bit values, laid out and read like that kernel's K tile) just ahead of the unit's first tile, so that no
+    // ordinary load at a unit boundary makes the wave wait for everything it has in flight.
+    using GQ = Geo<D>;
+    constexpr int kQBytes = GQ::kQueryBytes;
+    constexpr int QL = kQBytes / 1024;             // wave-wide 1 KB fetches per query image
     u32x4 qb[KJ];
-    auto load_q = [&](int b, int kvh) {
-        const uint16_t* qrow = reinterpret_cast<const uint16_t*>(p.q) + (int64_t)b * p.q_stride_b +
-                               (int64_t)(kvh * G + min(lr, G - 1)) * p.q_stride_h;
+    uint32_t qoff[QL], qread[KJ];
 #pragma unroll
-        for (int j = 0; j < KJ; ++j) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(qrow + (4 * j + lq) * 8);
-            qb[j] = lr < G ? v : u32x4{0, 0, 0, 0};
-        }
-    };
-    load_q(ca.b, ca.kvh);
+    for (int r = 0; r < QL; ++r) {
+        const int t = r * GQ::kRowsPerLoad + lane / GQ::kChunks, stored = lane % GQ::kChunks;
+        qoff[r] = (uint32_t)((int64_t)min(t, G - 1) * p.q_stride_h * 2 + ((stored ^ GQ::swz_k(t)) << 4));
+    }
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) qread[j] = lr * GQ::kRowBytes + (((4 * j + lq) ^ GQ::swz_k(lr)) << 4);
     const unsigned long long t_scan = traced ? wall_clock64() : 0;
 
     // ---- per-lane byte offsets, loop invariant
@@ -177,6 +182,15 @@ __global__ __launch_bounds__(kWaveSize) void attn_kv8_kernel(AttnParams p) {
     }
 
     const uint32_t ring_addr = (uint32_t)(uintptr_t)KVP_LDS(smem);
+    unsigned char* qring = smem + NS * kStageBytes;                     // query images behind the stages
+    const uint32_t qring_addr = ring_addr + NS * kStageBytes;
+    auto issue_q = [&](const Cursor& c, int slot) {
+        const unsigned char* qrow = reinterpret_cast<const unsigned char*>(p.q) +
+                                    ((int64_t)c.b * p.q_stride_b + (int64_t)c.kvh * G * p.q_stride_h) * 2;
+#pragma unroll
+        for (int r = 0; r < QL; ++r)
+            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(qrow + qoff[r]), KVP_LDS(qring + slot * kQBytes + r * 1024), 16, 0, 0);
+    };
     const unsigned char* kcache = reinterpret_cast<const unsigned char*>(p.k_cache);
     const unsigned char* vcache = reinterpret_cast<const unsigned char*>(p.v_cache);
 
@@ -211,9 +225,15 @@ __global__ __launch_bounds__(kWaveSize) void attn_kv8_kernel(AttnParams p) {
     // ---- prologue: the prefetch cursor runs PD tiles ahead of the consume cursor
     Cursor cp = ca;
     int64_t rp = r0;
+    bool cp_new_unit = true;                      // cp stands on the first tile of a unit's piece: its queries go first
+    int q_issue = 0, q_read = 0;
     auto issue_next = [&](int stage) {
+        if (cp_new_unit) {
+            issue_q(cp, q_issue);
+            q_issue = q_issue + 1 == NS ? 0 : q_issue + 1;
+        }
         issue(cp, stage);
-        if (++rp < r1) advance(cp);
+        cp_new_unit = ++rp < r1 ? advance(cp) : false;
     };
     if constexpr (PD > 0) {
 #pragma unroll
@@ -224,6 +244,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_kv8_kernel(AttnParams p) {
     int stage = 0;
     int piece_first_j = ca.j;
     bool piece_at_range_start = true;
+    bool ca_new_unit = true;
     for (int64_t r = r0; r < r1; ++r) {
         if constexpr (PD == 0) {
             issue_next(0);
@@ -238,6 +259,20 @@ __global__ __launch_bounds__(kWaveSize) void attn_kv8_kernel(AttnParams p) {
             }
         }
         asm volatile("" ::: "memory");
+        if (ca_new_unit) {      // the unit's queries landed before its first tile did: into registers, rows past G zeroed
+            const uint32_t qa = qring_addr + q_read * kQBytes;
+            if constexpr (KJ == 4) {
+                lds_read_b128_x4(qb[0], qb[1], qb[2], qb[3], qa + qread[0], qa + qread[1], qa + qread[2], qa + qread[3]);
+                lds_wait_k<0>(qb[0], qb[1], qb[2], qb[3]);
+            } else {
+                lds_read_b128_x2(qb[0], qb[1], qa + qread[0], qa + qread[1]);
+                lds_wait_k<0>(qb[0], qb[1]);
+            }
+#pragma unroll
+            for (int j = 0; j < KJ; ++j) qb[j] = lr < G ? qb[j] : u32x4{0, 0, 0, 0};
+            q_read = q_read + 1 == NS ? 0 : q_read + 1;
+            ca_new_unit = false;
+        }
         const uint32_t st = ring_addr + stage * kStageBytes;
 
         // ---- every LDS read of the tile: raw K operands of both row blocks, then the transposed raw V operands
@@ -331,11 +366,8 @@ __global__ __launch_bounds__(kWaveSize) void attn_kv8_kernel(AttnParams p) {
             piece_at_range_start = false;
         }
         if (!range_end) {
-            advance(ca);
-            if (unit_end) {
-                piece_first_j = 0;
-                load_q(ca.b, ca.kvh);
-            }
+            ca_new_unit = advance(ca);
+            if (ca_new_unit) piece_first_j = 0;
         }
     }
     if (traced && lane == 0) {
@@ -347,7 +379,7 @@ __global__ __launch_bounds__(kWaveSize) void attn_kv8_kernel(AttnParams p) {
 
 template <Elem E, int D, int BS, int PD>
 int launch_one(const AttnParams& p, hipStream_t stream) {
-    const size_t lds = (size_t)(PD + 1) * Geo8<D>::kStageBytes;
+    const size_t lds = (size_t)kv8_worker_lds_bytes(PD, D);
     auto kern = attn_kv8_kernel<E, D, BS, PD>;
     hipLaunchKernelGGL(kern, dim3(p.num_workers), dim3(kWaveSize), lds, stream, p);
     return 0;
@@ -372,6 +404,11 @@ int launch_shape(const AttnParams& p, int d, int bs, hipStream_t stream) {
 }
 
 }  // namespace
+
+// LDS bytes one worker (wave) holds: its ring of fetched tile pairs (32 tokens each) and as many query images.
+int kv8_worker_lds_bytes(int prefetch_distance, int d) {
+    return (prefetch_distance + 1) * (d == 128 ? Geo8<128>::kStageBytes + Geo<128>::kQueryBytes : Geo8<64>::kStageBytes + Geo<64>::kQueryBytes);
+}
 
 // Returns 0 or -1 (no such instantiation).  elem is the type of q and out.
 int launch_attn_kv8(const AttnParams& p, int elem, int d, int bs, hipStream_t stream) {

@@ -31,6 +31,13 @@
 // Computing the transposed products keeps the head index on lane % 16 from the logits to
 // the output accumulators, so the softmax rescale is a per-lane multiply.
 //
+// Queries.  The Q rows of a unit take the same road as its tiles: when the look-ahead cursor enters a unit, the unit's
+// G query rows are fetched by global_load_lds into a ring of PD + 1 query images (laid out like a K tile, rows past
+// G repeating the last one), just ahead of the fetch of the unit's first tile; they have landed when that tile has,
+// and are read into registers there.  An ordinary load of Q at the unit boundary would make the wave wait for
+// everything it has in flight, the stores of the unit it just finished included: measured 3 to 6 us per boundary
+// inside a worker's range, 1.5 to 3 % of a launch on batches of ragged lengths.
+//
 // LDS layout of a stage: K tile then V tile, each 16 rows x 2d bytes, written by
 // global_load_lds_dwordx4 (lane i of load r lands at r*1024 + i*16).  Bank conflicts are
 // avoided by permuting which 16-byte chunk of a row each lane fetches: with C = d/8 chunks per
@@ -68,6 +75,7 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
     constexpr int LPT = kTileBytes / 1024;      // wave-wide 1 KB fetches per K (or V) tile
     constexpr int LOADS = 2 * LPT;              // per tile pair
     constexpr int kPartialStride = G_::kPartialStride;
+    constexpr int kQBytes = G_::kQueryBytes;    // query image of a unit; NS of them behind the stages
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int worker = blockIdx.x;
@@ -102,21 +110,22 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
         ca.kvh = rem / ca.ntiles;
         ca.j = rem - ca.kvh * ca.ntiles;
     }
-    auto advance = [&](Cursor& c) {              // step to the next flat tile; the caller knows one exists
-        if (++c.j < c.ntiles) return;
+    auto advance = [&](Cursor& c) {              // step to the next flat tile (the caller knows one exists); true when it belongs to another unit
+        if (++c.j < c.ntiles) return false;
         c.j = 0;
-        if (++c.kvh < Hkv) return;
+        if (++c.kvh < Hkv) return true;
         c.kvh = 0;
         do {
             ++c.b;
             c.n = clamp_len(cl[c.b], max_len);
             c.ntiles = tiles_of(c.n, kTileShift);
         } while (c.ntiles == 0 && c.b + 1 < p.B);
+        return true;
     };
 
     const unsigned char* kcache = reinterpret_cast<const unsigned char*>(p.k_cache);
     const unsigned char* vcache = reinterpret_cast<const unsigned char*>(p.v_cache);
-    volatile uint32_t* progress = reinterpret_cast<volatile uint32_t*>(smem + NS * kStageBytes);   // TOUCH only
+    volatile uint32_t* progress = reinterpret_cast<volatile uint32_t*>(smem + NS * (kStageBytes + kQBytes));   // TOUCH only
     if constexpr (TOUCH) {
         if (threadIdx.x == 0) *progress = 0;       // tiles the consumer has started
         __syncthreads();
@@ -151,18 +160,9 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
         }
     }
 
-    // ---- Q^T operand of a unit: lane (g = lr, lq) holds Q[g][(4j + lq) * 8 .. +8], zero rows for g >= G
+    // ---- Q^T operand of a unit: lane (g = lr, lq) holds Q[g][(4j + lq) * 8 .. +8], zero rows for g >= G; read from
+    // the unit's query image in LDS (below)
     u32x4 qb[KJ];
-    auto load_q = [&](int b, int kvh) {
-        const uint16_t* qrow = reinterpret_cast<const uint16_t*>(p.q) + (int64_t)b * p.q_stride_b +
-                               (int64_t)(kvh * G + min(lr, G - 1)) * p.q_stride_h;
-#pragma unroll
-        for (int j = 0; j < KJ; ++j) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(qrow + (4 * j + lq) * 8);
-            qb[j] = lr < G ? v : u32x4{0, 0, 0, 0};
-        }
-    };
-    load_q(ca.b, ca.kvh);
     const unsigned long long t_scan = traced ? wall_clock64() : 0;
 
     // ---- per-lane byte offsets, loop invariant
@@ -174,6 +174,13 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
         const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
         koff[r] = t * kRowBytes + ((stored ^ G_::swz_k(t)) << 4);
         voff[r] = t * kRowBytes + ((stored ^ G_::swz_v(t)) << 4);
+    }
+    // the query image is fetched like a K tile whose row t is query row min(t, G - 1) of the unit
+    uint32_t qoff[LPT];
+#pragma unroll
+    for (int r = 0; r < LPT; ++r) {
+        const int t = r * G_::kRowsPerLoad + lane / G_::kChunks, stored = lane % G_::kChunks;
+        qoff[r] = (uint32_t)((int64_t)min(t, G - 1) * p.q_stride_h * 2 + ((stored ^ G_::swz_k(t)) << 4));
     }
     // K read for MFMA j: row lr, logical chunk 4j + lq  ->  stored chunk (4j + lq) ^ swizzle(lr)
     uint32_t kread[KJ];
@@ -188,6 +195,15 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
         vread[cb] = kTileBytes + vt * kRowBytes + (((2 * cb + (lane % 4) / 2) ^ G_::swz_v(vt)) << 4) + ((lane % 2) << 3);
 
     const uint32_t ring_addr = (uint32_t)(uintptr_t)KVP_LDS(smem);      // LDS byte address of the ring
+    unsigned char* qring = smem + NS * kStageBytes;                     // query images behind the stages
+    const uint32_t qring_addr = ring_addr + NS * kStageBytes;
+    auto issue_q = [&](const Cursor& c, int slot) {   // asynchronous fetch of a unit's query rows into a query image
+        const unsigned char* qrow = reinterpret_cast<const unsigned char*>(p.q) +
+                                    ((int64_t)c.b * p.q_stride_b + (int64_t)c.kvh * G * p.q_stride_h) * 2;
+#pragma unroll
+        for (int r = 0; r < LPT; ++r)
+            __builtin_amdgcn_global_load_lds(KVP_GLOBAL(qrow + qoff[r]), KVP_LDS(qring + slot * kQBytes + r * 1024), 16, 0, 0);
+    };
 
     auto issue = [&](const Cursor& c, int stage) {   // asynchronous fetch of one K tile and one V tile into a stage
         int phys = bt[(int64_t)c.b * p.bt_stride_b + c.j / TPB];   // only entries of tiles inside the range are read
@@ -215,9 +231,15 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
     // ---- prologue: the prefetch cursor runs PD tiles ahead of the consume cursor
     Cursor cp = ca;
     int64_t rp = r0;                              // flat index of the tile cp points at
+    bool cp_new_unit = true;                      // cp stands on the first tile of a unit's piece: its queries go first
+    int q_issue = 0, q_read = 0;                  // query images are used in turn, by the fetches and by the reads
     auto issue_next = [&](int stage) {
+        if (cp_new_unit) {
+            issue_q(cp, q_issue);
+            q_issue = q_issue + 1 == NS ? 0 : q_issue + 1;
+        }
         issue(cp, stage);
-        if (++rp < r1) advance(cp);
+        cp_new_unit = ++rp < r1 ? advance(cp) : false;
     };
     if constexpr (PD > 0) {
 #pragma unroll
@@ -228,6 +250,7 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
     int stage = 0;
     int piece_first_j = ca.j;                     // where the current piece of the current unit began
     bool piece_at_range_start = true;
+    bool ca_new_unit = true;                      // the consume cursor stands on the first tile of a unit's piece
     unsigned long long t_first = 0;               // traced: clock when the first tile pair of the range had landed
     for (int64_t r = r0; r < r1; ++r) {
         if constexpr (TOUCH) {
@@ -252,6 +275,20 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
         if constexpr (FETCH_ONLY) {
             if constexpr (PD > 0) { stage = stage + 1 == NS ? 0 : stage + 1; }
             continue;
+        }
+        if (ca_new_unit) {      // the unit's queries landed before its first tile did: into registers, rows past G zeroed
+            const uint32_t qa = qring_addr + q_read * kQBytes;
+            if constexpr (KJ == 4) {
+                lds_read_b128_x4(qb[0], qb[1], qb[2], qb[3], qa + kread[0], qa + kread[1], qa + kread[2], qa + kread[3]);
+                lds_wait_k<0>(qb[0], qb[1], qb[2], qb[3]);
+            } else {
+                lds_read_b128_x2(qb[0], qb[1], qa + kread[0], qa + kread[1]);
+                lds_wait_k<0>(qb[0], qb[1]);
+            }
+#pragma unroll
+            for (int j = 0; j < KJ; ++j) qb[j] = lr < G ? qb[j] : u32x4{0, 0, 0, 0};
+            q_read = q_read + 1 == NS ? 0 : q_read + 1;
+            ca_new_unit = false;
         }
         const uint32_t st = ring_addr + stage * kStageBytes;
         u32x4 ka[KJ];
@@ -346,11 +383,8 @@ __global__ __launch_bounds__(TOUCH ? 2 * kWaveSize : kWaveSize) void attn_mfma_k
             piece_at_range_start = false;
         }
         if (!range_end) {
-            advance(ca);
-            if (unit_end) {
-                piece_first_j = 0;
-                load_q(ca.b, ca.kvh);
-            }
+            ca_new_unit = advance(ca);
+            if (ca_new_unit) piece_first_j = 0;
         }
     }
     if (traced && lane == 0) {
@@ -549,10 +583,9 @@ int launch_fetch_probe(const AttnParams& p, int d, int bs, hipStream_t stream) {
     return -1;
 }
 
-// LDS bytes one worker (wave) holds at a prefetch distance: its ring of fetched tile pairs.  (The same for an
-// 8-bit cache, whose tiles hold twice the tokens in the same bytes.)
+// LDS bytes one worker (wave) holds at a prefetch distance: its ring of fetched tile pairs and as many query images.
 int mfma_worker_lds_bytes(int prefetch_distance, int d) {
-    const int stage = d == 128 ? Geo<128>::kStageBytes : Geo<64>::kStageBytes;
+    const int stage = d == 128 ? Geo<128>::kStageBytes + Geo<128>::kQueryBytes : Geo<64>::kStageBytes + Geo<64>::kQueryBytes;
     return (prefetch_distance + 1) * stage;
 }
 

@@ -81,22 +81,25 @@ int num_cus() {     // of the current device
 // arithmetic of its smaller tiles.  An 8-bit cache has tile pairs of the same bytes (32 tokens) and twice the
 // arithmetic per byte (the widening included): two waves cannot keep up (measured 120 us against 90 us with six
 // on the Llama-3-8B-shaped batch), so it runs six waves (head_dim 128) or eight to twelve (head_dim 64) at every
-// distance the LDS allows, and four where five would fit (an odd count, uneven over the four SIMDs, is 40 %
-// slower).  The two-phase variant moves one tile per step where the one-pass kernel moves a pair, so it wants
+// distance the LDS allows, and the even count below where an odd one would fit (an odd count, uneven over the
+// four SIMDs, is 40 % slower).  The two-phase variant moves one tile per step where the one-pass kernel moves a pair, so it wants
 // twice the waves for the same bytes in flight (measured best: 12 / 6 / 4 at distance 0 / 1 / 2).  Always capped
 // by the LDS the rings (and the two-phase variant's logits buffer) need.
 int waves_per_cu(int prefetch_distance, int d, bool kv8, int two_phase_group = 0) {
     const int lds_limit = kLdsBytesPerCU / (two_phase_group ? kvp::twophase_worker_lds_bytes(prefetch_distance, d, two_phase_group)
+                                            : kv8         ? kvp::kv8_worker_lds_bytes(prefetch_distance, d)
                                                             : kvp::mfma_worker_lds_bytes(prefetch_distance, d));
     int w = g_waves_per_cu.load();
     if (w <= 0) {
         if (two_phase_group) w = prefetch_distance == 0 ? 12 : prefetch_distance == 1 ? 6 : 4;
-        else if (kv8) w = d == 128 ? (prefetch_distance <= 2 ? 6 : 4) : (prefetch_distance == 0 ? 12 : 8);
+        else if (kv8) w = d == 128 ? 6 : (prefetch_distance == 0 ? 12 : 8);
         else if (d == 128) w = prefetch_distance <= 1 ? 6 : 2;
         else w = prefetch_distance <= 1 ? 8 : 4;
     }
+    const bool automatic = g_waves_per_cu.load() <= 0;
     w = w < lds_limit ? w : lds_limit;
     w = w < kMaxWavesPerCU ? w : kMaxWavesPerCU;
+    if (kv8 && automatic && w > 1 && (w & 1)) --w;     // an odd count is uneven over the four SIMDs (measured 40 % slower)
     return w;
 }
 
@@ -164,6 +167,8 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
         return fail(KV_ERR_INVALID, "kv_decode_attn: block_tables / context_lens batch differs from q");
     if (block_tables->shape[1] <= 0 || block_tables->shape[1] > (1 << 24))
         return fail(KV_ERR_INVALID, "kv_decode_attn: block table width out of range");
+    if (q->stride[1] < 0 || q->stride[1] * 2 * 15 + 512 > INT32_MAX)
+        return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: query head stride %lld out of range", (long long)q->stride[1]);
     if (q->stride[2] != 1 || out->stride[2] != 1 || block_tables->stride[1] != 1 || context_lens->stride[0] != 1)
         return fail(KV_ERR_INVALID, "kv_decode_attn: innermost stride must be 1");
     if (!dense_tile(k_cache) || !dense_tile(v_cache))

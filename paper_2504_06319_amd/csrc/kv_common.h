@@ -70,6 +70,7 @@ size_t layer_gemm_packed_partial_bytes(int N);
 void launch_zero_words(int* p, int n, hipStream_t stream);
 constexpr size_t kGemmTicketBytes = 4096;      // head of the workspace: one ticket word per 128-column tile of the dense layer
 int mfma_worker_lds_bytes(int prefetch_distance, int d);
+int kv8_worker_lds_bytes(int prefetch_distance, int d);
 size_t mfma_partial_bytes(int num_workers, int G, int d);
 constexpr int kMaxMfmaWorkers = 4096;
 constexpr int kMaxDevices = 64;                // device ordinals the library keeps state for

@@ -59,16 +59,16 @@ def test_waves_per_cu_follow_the_lds_budget():
     # flight per compute unit), never fewer than four at head_dim 64
     assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [6, 6, 2, 2, 2]
     assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [8, 8, 4, 4, 4]
-    # an explicit request is capped by LDS: a worker's ring is (distance + 1) x 8 KB at head_dim 128 (4 KB at
-    # 64), a compute unit has 160 KB
+    # an explicit request is capped by LDS: a worker holds (distance + 1) x 12 KB at head_dim 128 (a stage of 8 KB
+    # and a query image of 4 KB; 6 KB at head_dim 64; 8-bit caches: 8 KB and 4 KB), a compute unit has 160 KB
     # 8-bit cache: tile pairs of the same bytes (32 tokens), twice the arithmetic per byte: more waves
-    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [6, 6, 6, 4, 4]
-    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 64) for d in range(5)] == [12, 8, 8, 8, 8]
+    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [6, 6, 4, 2, 2]
+    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 64) for d in range(5)] == [12, 8, 8, 6, 4]
     kv.kv_decode_set_waves_per_cu(16)
     try:
-        assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [16, 10, 6, 5, 4]
-        assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [16, 10, 6, 5, 4]
-        assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [16, 16, 13, 10, 8]
+        assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [13, 6, 4, 3, 2]
+        assert [kv.kv_decode_get_waves_per_cu(d, 128) for d in range(5)] == [13, 6, 4, 3, 2]
+        assert [kv.kv_decode_get_waves_per_cu(d, 64) for d in range(5)] == [16, 13, 8, 6, 5]
         with pytest.raises(kv.KVError):
             kv.kv_decode_set_waves_per_cu(17)
     finally:

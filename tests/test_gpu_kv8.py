@@ -75,7 +75,7 @@ def test_every_prefetch_distance_gives_the_same_bits(pd):
     rng = np.random.default_rng(7)
     lens = rng.integers(1, 3000, 12).tolist()
     c = synth.make_case_kv8(cfg, 21, DEV, poison=True, lens=lens, k_scale=1.5, v_scale=0.75)
-    kv.kv_decode_set_waves_per_cu(4)        # the cuts depend on the worker count: keep it fixed
+    kv.kv_decode_set_waves_per_cu(2)        # the cuts depend on the worker count: one that fits the LDS at every distance
     try:
         got = run_hip(c, pd)
         ref = run_hip(c, 0)
