@@ -219,6 +219,7 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     p.num_workers = nw < kvp::kMaxMfmaWorkers ? nw : kvp::kMaxMfmaWorkers;
     p.xcd_skew = g_xcd_skew.load();
     p.plain_fetch = (!kv8 && !r->two_phase) ? g_plain_fetch.load() : 0;
+    p.rescale_slack = kvp::kRescaleSlack;
     p.l2_touch = (!kv8 && !r->two_phase && prefetch_distance == 0 && !p.plain_fetch) ? g_l2_touch.load() : 0;
     r->partial_bytes = kvp::mfma_partial_bytes(p.num_workers, G, (int)d);
     p.partials = nullptr;           // bound by bind_registered / bind_static

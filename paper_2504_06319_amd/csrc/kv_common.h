@@ -10,6 +10,10 @@ namespace kvp {
 
 constexpr int kWaveSize = 64;
 constexpr float kNegBig = -1.0e30f;       // "no token seen yet" running maximum (finite on purpose)
+// log2 units a head's running maximum may grow before the accumulators are rescaled (AttnParams::rescale_slack).
+// Swept at run time over 0, 1, 2, 4, 8 on the three benchmark batches: 2 is best or within 0.3 % of best on each
+// (against 0: +0.8 %, +0.1 %, +2.3 %); larger values cost the batch of few long sequences 1 %.
+constexpr float kRescaleSlack = 2.0f;
 constexpr float kLog2e = 1.4426950408889634f;
 
 // One attention call, resolved by the host.  Strides in elements.
@@ -38,6 +42,7 @@ struct AttnParams {
     int32_t plain_fetch;      // comparison mode: KV fetches without the non-temporal hint (benchmark shapes only)
     float scale_log2e;        // scale * log2(e) (* k_scale for an 8-bit cache): logits live in the base-2 domain
     float out_scale;          // multiplies every output row: 1, or v_scale for an 8-bit cache
+    float rescale_slack;      // log2 units a head's running maximum may grow before the accumulators are rescaled
 };
 
 enum class Elem : int { F16 = 0, BF16 = 1 };
