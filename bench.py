@@ -551,6 +551,7 @@ def main():
     cfg, cases = make_cases(args.workload, kv8=args.kv8)
     kvb = synth.kv_bytes(cases[0]["lens"], cfg["Hkv"], cfg["d"], 1 if args.kv8 else 2)
     step_on = attn_step(kv, cases, pd_on)
+    event_bracket_overhead(torch)              # measured (and cached) now: its idle milliseconds must not sit between pre-warm and timing
     warm_ms, warm_kernel_ms = prewarm(kv, torch, step_on, min_ms=args.prewarm_ms) if args.prewarm_ms > 0 else (0.0, 0.0)
     log(f"[bench] pre-warm: {warm_ms:.0f} ms of kernel time until the duration settled at {warm_kernel_ms:.4f} ms")
     ms, main_ms, main_ms_median = timed_steps(kv, torch, step_on, args.steps, args.warmup)
@@ -683,10 +684,20 @@ def main():
         del cases, step_on, step_off, legs
         torch.cuda.empty_cache()
         run, lkvb, lwb, lcfg, L = build_layer_stack(kv, torch, synth, dev)
-        passes = max(3, args.steps // 5)
-        for _ in range(3):
+        passes = max(8, args.steps // 5)
+        # untimed passes until the pass duration has settled (building 32 layers of cache leaves the chip cold):
+        # at least 6, at most 30, until three in a row agree within 1 %
+        warm = []
+        while len(warm) < 30:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
             run(pd_on, 0)
-        torch.cuda.synchronize()
+            b.record()
+            b.synchronize()
+            warm.append(a.elapsed_time(b))
+            if len(warm) >= 6 and max(warm[-3:]) <= 1.01 * min(warm[-3:]):
+                break
+        log(f"[bench] layer stack pre-warm: {len(warm)} passes, {warm[0]:.3f} -> {warm[-1]:.3f} ms")
         r = interleaved(kv, torch, [("on", nowaves, lambda i: run(pd_on, 0)), ("on_cross_layer_touch", nowaves, lambda i: run(pd_on, 1)),
                                     ("off", nowaves, lambda i: run(0, 0))], rounds=passes, block=1, lead_in=1, kernel_events=False)
         ls = {}
@@ -703,7 +714,7 @@ def main():
         ls["layers"] = L
         ls["kv_bytes_per_pass"] = lkvb
         ls["weight_bytes_per_pass"] = lwb
-        ls["method"] = f"{passes} interleaved rounds of single passes, medians (3 untimed passes first)"
+        ls["method"] = f"{passes} interleaved rounds of single passes, medians ({len(warm)} untimed passes first, until three in a row agreed within 1 %)"
         result["layer_stack"] = ls
         del run
         torch.cuda.empty_cache()
