@@ -154,14 +154,20 @@ __global__ __launch_bounds__(256) void layer_gemm_packed_kernel(const uint16_t* 
 
     const uint32_t ring_addr = (uint32_t)(uintptr_t)KVP_PK_LDS(smem);
 
-    // x fetch r (0..7) of a slab lands rows 16 r .. 16 r + 15; this wave issues r = 2 wave and 2 wave + 1.  A lane
-    // lands row 16 r + lane / 4 at stored chunk lane % 4 and fetches the logical chunk stored ^ (row / 4) % 4; rows
-    // >= M re-read row M - 1 (their products are never stored)
+    // x fetch r (0..7) of a slab fills the 1 KB of m-block r; this wave issues r = 2 wave and 2 wave + 1.  A lane
+    // lands position lane / 4 (0..15) of the m-block at stored chunk lane % 4.  Position p holds matrix row
+    // 2 (p % 8) + p / 8 of the m-block (even rows first, then odd rows) and stored chunk c holds the row's logical
+    // chunk c ^ f(p), f(p) = 2 (p / 4 % 2) + p / 8: a ds_read_b128 is served 16 lanes at a time, and both for
+    // 16 consecutive lanes and for every other lane of a half wave (what the conflict counter points to: with rows
+    // in natural order it read 4 conflict cycles in every 8) those 16 lanes then cover all 64 banks.  Rows >= M
+    // re-read row M - 1 (their products are never stored)
+    auto swz = [](int pos) { return 2 * ((pos / 4) % 2) + pos / 8; };
     uint32_t xoff[kPkXOwn];
 #pragma unroll
     for (int i = 0; i < kPkXOwn; ++i) {
-        const int row = 16 * (kPkXOwn * wave + i) + lane / 4;
-        const int logical = (lane % 4) ^ ((row / 4) % 4);
+        const int pos = lane / 4;
+        const int row = 16 * (kPkXOwn * wave + i) + 2 * (pos % 8) + pos / 8;
+        const int logical = (lane % 4) ^ swz(pos);
         xoff[i] = (uint32_t)(min(row, M - 1) * ldx * 2 + logical * 16);
     }
     const unsigned char* xg = reinterpret_cast<const unsigned char*>(x) + (int64_t)khalf * STEPS * kPkBK * 2;
@@ -174,8 +180,10 @@ __global__ __launch_bounds__(256) void layer_gemm_packed_kernel(const uint16_t* 
         constexpr int nb = decltype(nb_tag)::value;
         pk_load_w<nb * 1024, PLAIN>(slot[nb], wg + (int64_t)kstep * 4096, w_lane);
     };
-    // A operand of m-block mb: row 16 mb + lr, logical chunk lq -> stored chunk lq ^ (lr / 4) % 4; + 1024 per m-block
-    const uint32_t a_off = lr * 64 + ((lq ^ ((lr / 4) % 4)) << 4);
+    // A operand of m-block mb: row 16 mb + lr sits at position lr / 2 + 8 (lr % 2), its logical chunk lq at stored
+    // chunk lq ^ f(position); + 1024 per m-block
+    const int a_pos = lr / 2 + 8 * (lr % 2);
+    const uint32_t a_off = a_pos * 64 + ((lq ^ swz(a_pos)) << 4);
 
     auto issue_x = [&](int step) {
         const unsigned char* xt = xg + (int64_t)step * (kPkBK * 2);
