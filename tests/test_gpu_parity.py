@@ -326,6 +326,25 @@ def test_large_logits_do_not_overflow():
     check_case(c, 1, "large logits")
 
 
+@pytest.mark.parametrize("step", [0.05, 0.25, 0.5, -0.5])
+@pytest.mark.parametrize("pd", [0, 2])
+def test_logits_that_keep_growing_or_falling(step, pd):
+    """The running maximum creeps up by less than the kernel's rescale slack per tile, or by more, or never moves
+    after the first token: the accumulators are rescaled only now and then, and the result must not care."""
+    n = 700
+    c = synth.make_case(_cfg(8, 2, 128, 16, "bf16"), 43, DEV, poison=True, lens=[n, 333])
+    bt = c["block_tables"].cpu().numpy()
+    ramp = (torch.arange(n, dtype=torch.float32) * step / 16.0)
+    for t in range(n):
+        blk = int(bt[0, t // 16])
+        c["k_cache"][blk, :, t % 16, :] = 0
+        c["k_cache"][blk, :, t % 16, 0] = ramp[t]
+    c["q"][0] = 0
+    c["q"][0, :, 0] = 16.0                   # logit of token t = step * t (natural log units), before bf16 rounding of K
+    c["scale"] = 1.0
+    check_case(c, pd, f"ramp {step}")
+
+
 def test_one_million_token_context():
     """A single unit of 65 537 tiles: every worker holds one piece of it and the merge kernel sees 1 536 pieces."""
     n = (1 << 20) + 7
