@@ -76,7 +76,7 @@ typedef struct kv_tensor {
  */
 #define KV_MAX_PREFETCH_DISTANCE 4
 /* prefetch_distance value that lets the library choose: the distance (and the occupancy that goes with it) measured
- * fastest on this chip for the cache type: 2 for 16-bit caches, 0 for kv_decode_attn_kv8. */
+ * fastest on this chip for the cache type: 2 for 16-bit caches, 1 for kv_decode_attn_kv8. */
 #define KV_PREFETCH_AUTO (-1)
 int kv_decode_attn(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cache,
                    const kv_tensor* block_tables, const kv_tensor* context_lens, kv_tensor* out,
@@ -225,8 +225,8 @@ int kv_decode_get_waves_per_cu(int prefetch_distance, int head_dim);
  * two-phase variant depends (kv_decode_get_waves_per_cu assumes 16 there); 0 for invalid arguments. */
 int kv_decode_get_waves_per_cu_for(int prefetch_distance, int head_dim, int q_heads_per_kv_head);
 /* The same for kv_decode_attn_kv8 (stages of the same bytes, holding 32 tokens; twice the arithmetic
- * per byte, so more waves: at head_dim 128 6 waves, at head_dim 64 12 waves at distance 0 and 8
- * beyond, fewer where the LDS caps them, and then an even number). */
+ * per byte, so more waves: at head_dim 128 6 waves at distance 0 and 3 with a look-ahead, at head_dim 64
+ * 8 waves, fewer where the LDS caps them, and above four an even number). */
 int kv_decode_get_waves_per_cu_kv8(int prefetch_distance, int head_dim);
 
 /*

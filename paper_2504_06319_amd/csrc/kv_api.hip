@@ -79,10 +79,11 @@ int num_cus() {     // of the current device
 // keeps max(1, distance) tile pairs of 8 KB (head_dim 128) or 4 KB (head_dim 64) in flight, so deep look-ahead
 // wants few waves and no look-ahead wants many; head_dim 64 needs at least four waves to keep up with the
 // arithmetic of its smaller tiles.  An 8-bit cache has tile pairs of the same bytes (32 tokens) and twice the
-// arithmetic per byte (the widening included): two waves cannot keep up (measured 120 us against 90 us with six
-// on the Llama-3-8B-shaped batch), so it runs six waves (head_dim 128) or eight to twelve (head_dim 64) at every
-// distance the LDS allows, and the even count below where an odd one would fit (an odd count, uneven over the
-// four SIMDs, is 40 % slower).  The two-phase variant moves one tile per step where the one-pass kernel moves a pair, so it wants
+// arithmetic per byte: two waves cannot keep up (115 us on the Llama-3-8B-shaped batch), three with a look-ahead of
+// one can (85 us, and a merge over 768 workers: step 90.5 us), six without look-ahead come close (87 us, step
+// 96 us with the merge over 1536 workers); head_dim 64: eight waves at every distance (step 55.0 us at distance
+// 1, 58.1 at 0; twelve at distance 0: 66.6).  Above four, an odd count (uneven over the four SIMDs) is 40 % slower
+// than the even count below it.  The two-phase variant moves one tile per step where the one-pass kernel moves a pair, so it wants
 // twice the waves for the same bytes in flight (measured best: 12 / 6 / 4 at distance 0 / 1 / 2).  Always capped
 // by the LDS the rings (and the two-phase variant's logits buffer) need.
 int waves_per_cu(int prefetch_distance, int d, bool kv8, int two_phase_group = 0) {
@@ -92,14 +93,14 @@ int waves_per_cu(int prefetch_distance, int d, bool kv8, int two_phase_group = 0
     int w = g_waves_per_cu.load();
     if (w <= 0) {
         if (two_phase_group) w = prefetch_distance == 0 ? 12 : prefetch_distance == 1 ? 6 : 4;
-        else if (kv8) w = d == 128 ? 6 : (prefetch_distance == 0 ? 12 : 8);
+        else if (kv8) w = d == 128 ? (prefetch_distance == 0 ? 6 : 3) : 8;
         else if (d == 128) w = prefetch_distance <= 1 ? 6 : 2;
         else w = prefetch_distance <= 1 ? 8 : 4;
     }
     const bool automatic = g_waves_per_cu.load() <= 0;
     w = w < lds_limit ? w : lds_limit;
     w = w < kMaxWavesPerCU ? w : kMaxWavesPerCU;
-    if (kv8 && automatic && w > 1 && (w & 1)) --w;     // an odd count is uneven over the four SIMDs (measured 40 % slower)
+    if (kv8 && automatic && w > 4 && (w & 1)) --w;     // above four an odd count is uneven over the four SIMDs (measured 40 % slower)
     return w;
 }
 
@@ -179,9 +180,9 @@ int resolve(const kv_tensor* q, const kv_tensor* k_cache, const kv_tensor* v_cac
     const int G = (int)(Hq / num_kv_heads);
     if (G > 16) return fail(KV_ERR_UNSUPPORTED, "kv_decode_attn: %d query heads per kv head exceeds 16", G);
     // KV_PREFETCH_AUTO: the distance measured best for the cache type, at the occupancy that goes with it (16-bit
-    // caches: two tiles ahead with two waves per compute unit; 8-bit caches need six waves for their arithmetic, and
-    // six waves' own requests already fill the memory system: no look-ahead)
-    if (prefetch_distance == KV_PREFETCH_AUTO) prefetch_distance = kv8 ? 0 : 2;
+    // caches: two tiles ahead with two waves per compute unit; 8-bit caches: one tile ahead with three, eight at
+    // head_dim 64: see waves_per_cu)
+    if (prefetch_distance == KV_PREFETCH_AUTO) prefetch_distance = kv8 ? 1 : 2;
     if (prefetch_distance < 0 || prefetch_distance > KV_MAX_PREFETCH_DISTANCE)
         return fail(KV_ERR_INVALID, "kv_decode_attn: prefetch_distance %d outside 0..%d (or KV_PREFETCH_AUTO)", prefetch_distance, KV_MAX_PREFETCH_DISTANCE);
     // 128-bit loads need 16-byte aligned rows

@@ -62,8 +62,8 @@ def test_waves_per_cu_follow_the_lds_budget():
     # an explicit request is capped by LDS: a worker holds (distance + 1) x 12 KB at head_dim 128 (a stage of 8 KB
     # and a query image of 4 KB; 6 KB at head_dim 64; 8-bit caches: 8 KB and 4 KB), a compute unit has 160 KB
     # 8-bit cache: tile pairs of the same bytes (32 tokens), twice the arithmetic per byte: more waves
-    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [6, 6, 4, 2, 2]
-    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 64) for d in range(5)] == [12, 8, 8, 6, 4]
+    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [6, 3, 3, 3, 2]
+    assert [kv.kv_decode_get_waves_per_cu_kv8(d, 64) for d in range(5)] == [8, 8, 8, 6, 4]
     kv.kv_decode_set_waves_per_cu(16)
     try:
         assert [kv.kv_decode_get_waves_per_cu_kv8(d, 128) for d in range(5)] == [13, 6, 4, 3, 2]

@@ -430,7 +430,7 @@ def test_l2_touch_wave_on_a_full_size_configuration():
 
 
 def test_automatic_prefetch_distance_is_the_measured_best_one():
-    """KV_PREFETCH_AUTO resolves to distance 2 on a 16-bit cache and to distance 0 on an 8-bit one: the bits of those
+    """KV_PREFETCH_AUTO resolves to distance 2 on a 16-bit cache and to distance 1 on an 8-bit one: the bits of those
     explicit calls."""
     cfg = _cfg(8, 2, 128, 16, "bf16")
     lens = [900, 0, 17, 2500, 64, 1]
@@ -438,7 +438,7 @@ def test_automatic_prefetch_distance_is_the_measured_best_one():
     assert torch.equal(run_hip(c, kv.KV_PREFETCH_AUTO).view(torch.int16), run_hip(c, 2).view(torch.int16))
     c8 = synth.make_case_kv8(cfg, 311, DEV, poison=True, lens=lens, k_scale=0.5, v_scale=2.0)
     outs = []
-    for pd in (kv.KV_PREFETCH_AUTO, 0):
+    for pd in (kv.KV_PREFETCH_AUTO, 1):
         out = torch.full_like(c8["q"], float("nan"))
         kv.kv_decode_attn_kv8(c8["q"], c8["k_cache"], c8["v_cache"], c8["block_tables"], c8["context_lens"], out, c8["scale"],
                               c8["k_scale"], c8["v_scale"], 2, 16, pd)
