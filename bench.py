@@ -435,6 +435,9 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=1, choices=[1, 2, 3])
+    ap.add_argument("--head-dim", type=int, default=0, choices=[0, 64, 128],
+                    help="run the chosen workload with this head_dim instead of its own (64: the half-size tiles of the "
+                         "other geometry; the workload name gets a suffix)")
     ap.add_argument("--prefetch-distance", type=int, default=None)
     ap.add_argument("--waves-per-cu", type=int, default=0, help="persistent waves per compute unit (0 = automatic)")
     ap.add_argument("--prewarm-ms", type=float, default=50.0,
@@ -497,7 +500,10 @@ def main():
         kv.kv_decode_set_fetch_policy(kv.KV_FETCH_PLAIN)
 
     def make_cases(index, copies=2, kv8=False):
-        cfg = synth.CONFIGS[index]
+        cfg = dict(synth.CONFIGS[index])
+        if args.head_dim and args.head_dim != cfg["d"]:
+            cfg["d"] = args.head_dim
+            cfg["name"] += f"_head_dim_{args.head_dim}"
         out = []
         make = synth.make_case_kv8 if kv8 else synth.make_case
         for i in range(copies):      # distinct cache copies so no launch re-reads what the last one left in cache
